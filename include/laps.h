@@ -1,0 +1,233 @@
+/*
+ * laps.h - C ABI of the MI355X (gfx950) ragged-prefill hot path behind LAPS-style
+ * length-aware prefill scheduling.
+ *
+ * The paper (LAPS, "A Length-Aware-Prefill LLM Serving System") defines the scheduling:
+ * requests are classified by prompt length into a short and a long queue (Section 3.2,
+ * "Mutual exclusion"), short requests are padded into a grid of (length, batch size)
+ * buckets, one captured graph per bucket (Section 3.1, "Graph capture and bucketization"),
+ * batches are matched to a captured shape under a memory budget or fall back to the
+ * standard path (Algorithm 1), and long requests advance alone in fixed-size chunks
+ * (Section 3.2, deadline-free mode).  What runs under that schedule is the prefill forward:
+ * "incremental causal attention and FFN" over L new tokens that also attend to H cached
+ * historical tokens (Section 2.1, latency model) - one decoder layer stack of the Qwen2.5
+ * family the paper serves (Section 4.1).  This library is that forward plus the integer plan.
+ *
+ * Conventions
+ *   - Every function returns LAPS_OK (0) or a negative LAPS_E* code; laps_last_error()
+ *     gives a thread-local message for the last failure.  Nothing throws across the ABI.
+ *   - "dev" pointers are device (HBM) addresses on the context's GPU; "host" pointers are
+ *     ordinary host memory.  The caller owns every buffer it passes.  The library owns
+ *     laps_ctx, laps_plan, laps_graph and what those allocate internally.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  laps_prefill_*,
+ *     laps_graph_stage and laps_graph_replay only enqueue work: they never synchronise the
+ *     stream and never allocate device memory.
+ *   - bf16 = upper 16 bits of an IEEE float32, round-to-nearest-even on conversion.
+ *   - Layer math (all accumulation fp32): r = rmsnorm(x; ln1); [q,k,v] = r W_qkv^T (+b);
+ *     rotate-half RoPE with theta on q,k at absolute position prefix_len+t; causal grouped-
+ *     query attention over cached prefix + new tokens, scale 1/sqrt(head_dim), query head h
+ *     uses kv head h / (n_q/n_kv); x1 = x + attn W_o^T; r2 = rmsnorm(x1; ln2);
+ *     y = x1 + (silu(r2 W_g^T) * (r2 W_u^T)) W_d^T.  The residual stream is fp32; q, k, v,
+ *     normed rows, attention output and the MLP activation are stored as bf16.
+ *
+ * KV cache layout (per layer; page_size = 16 tokens):
+ *     k_pool: [n_pages][n_kv_heads][16 tokens][head_dim]  bf16   (keys already rotated)
+ *     v_pool: [n_pages][n_kv_heads][head_dim][16 tokens]  bf16   (transposed inside the page)
+ *   page_table[s][j] is the pool page holding logical positions 16j..16j+15 of sequence s.
+ *   Use laps_kv_scatter / laps_kv_gather to move token-major K/V in and out of pools.
+ */
+#ifndef LAPS_H
+#define LAPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LAPS_OK 0
+#define LAPS_EINVAL (-1) /* bad shape, unsorted grid, new_len < 1, prefix_len < 0, NULL where not allowed */
+#define LAPS_ENOMEM (-2) /* host or device allocation failed, or workspace too small */
+#define LAPS_EHIP (-3)   /* a HIP call failed; laps_last_error() names it */
+
+#define LAPS_PAGE 16
+
+typedef struct laps_ctx laps_ctx;
+typedef struct laps_plan laps_plan;
+typedef struct laps_graph laps_graph;
+
+/* Shape of one decoder layer stack.  Requirements: head_dim in {64, 128}; n_q_heads a
+ * multiple of n_kv_heads; hidden, n_q_heads*head_dim and intermediate multiples of 64;
+ * (n_q_heads + 2 n_kv_heads)*head_dim, hidden and 2*intermediate multiples of 128;
+ * page_size == 16. */
+typedef struct laps_model_cfg {
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, intermediate, n_layers;
+    int32_t page_size;    /* must be LAPS_PAGE */
+    int32_t has_qkv_bias; /* 0: b_qkv ignored */
+    float rope_theta;     /* e.g. 1e6 */
+    float rms_eps;        /* e.g. 1e-6 */
+} laps_model_cfg;
+
+/* Device pointers to one layer's bf16 weights, all [out, in] row-major:
+ * ln1_w [hidden]; w_qkv [(n_q+2n_kv)*hd, hidden] (q heads, then k heads, then v heads);
+ * b_qkv [(n_q+2n_kv)*hd] or NULL; w_o [hidden, n_q*hd]; ln2_w [hidden];
+ * w_gate_up [2*intermediate, hidden] as written by laps_pack_gate_up; w_down [hidden, intermediate]. */
+typedef struct laps_layer_weights {
+    const void *ln1_w, *w_qkv, *b_qkv, *w_o, *ln2_w, *w_gate_up, *w_down;
+} laps_layer_weights;
+
+/* ------------------------------------------------------------------ bucket plan (host, integer)
+ * Section 3.2 "Mutual exclusion" (classification by length), Section 3.1 (bucket grid, padding
+ * to a bucket, grouping by the same bucket), Algorithm 1 (captured shape with depth >= batch
+ * depth within the budget, else the standard path), deadline-free mode (fixed-size long chunks).
+ *
+ * Rules: request i is SHORT iff new_len[i] <= short_max_len (new tokens only; the cached prefix
+ * does not count), else LONG.  A short request goes to the smallest length bucket >= new_len.
+ * Per length bucket L_b (ascending), its requests (arrival order) are covered by graph depths
+ * from `depths` with depth*L_b <= token_budget, choosing the multiset that minimises (number of
+ * launches, total padded rows) and prefers larger depths first; batches are emitted larger depth
+ * first and filled in arrival order.  If no depth fits the budget the bucket's requests are
+ * split, in order, into the fewest contiguous groups whose un-padded token total is within the
+ * budget (a single request may exceed it) and marked graph_ok = 0 (run un-captured, un-padded).
+ * A long request is cut into ceil(new_len/long_chunk) chunks, all long_chunk except the last. */
+typedef struct laps_plan_params {
+    int32_t short_max_len;      /* >= 1 and <= len_buckets[n_len_buckets-1] */
+    int32_t n_len_buckets;
+    const int32_t* len_buckets; /* host, strictly ascending, >= 1 */
+    int32_t n_depths;
+    const int32_t* depths;      /* host, strictly ascending, >= 1 */
+    int32_t token_budget;       /* M: padded new tokens one captured graph may hold, >= 1 */
+    int32_t long_chunk;         /* C_l >= 1 */
+} laps_plan_params;
+
+/* new_len, prefix_len: host arrays [n_req]; new_len >= 1, prefix_len >= 0; n_req >= 0.
+ * On success *out is a plan to be released with laps_plan_free.  Deterministic, no GPU use. */
+int laps_plan_buckets(const laps_plan_params* params, int32_t n_req, const int32_t* new_len,
+                      const int32_t* prefix_len, laps_plan** out);
+void laps_plan_free(laps_plan* plan);
+/* Accessors return host pointers valid until laps_plan_free. */
+int32_t laps_plan_n_requests(const laps_plan* plan);
+const int32_t* laps_plan_req_class(const laps_plan* plan);   /* [n_req] 0 short, 1 long */
+const int32_t* laps_plan_req_bucket(const laps_plan* plan);  /* [n_req] length-bucket index, -1 if long */
+const int32_t* laps_plan_req_batch(const laps_plan* plan);   /* [n_req] batch index, -1 if long */
+const int32_t* laps_plan_req_row(const laps_plan* plan);     /* [n_req] slot inside its batch, -1 if long */
+int32_t laps_plan_n_batches(const laps_plan* plan);
+const int32_t* laps_plan_batch_len_bucket(const laps_plan* plan); /* [n_batches] L_b (tokens) */
+const int32_t* laps_plan_batch_depth(const laps_plan* plan);      /* [n_batches] graph depth, or group size if graph_ok=0 */
+const int32_t* laps_plan_batch_graph_ok(const laps_plan* plan);   /* [n_batches] */
+const int32_t* laps_plan_batch_req_offset(const laps_plan* plan); /* [n_batches+1] into batch_req_ids */
+const int32_t* laps_plan_batch_req_ids(const laps_plan* plan);    /* request ids, batch by batch */
+int32_t laps_plan_n_long(const laps_plan* plan);
+const int32_t* laps_plan_long_req(const laps_plan* plan);          /* [n_long] request id */
+const int32_t* laps_plan_long_chunk_offset(const laps_plan* plan); /* [n_long+1] into long_chunk_len */
+const int32_t* laps_plan_long_chunk_len(const laps_plan* plan);    /* chunk lengths, request by request */
+
+/* ------------------------------------------------------------------ context
+ * Binds a model shape to the current HIP device and builds the fp64-evaluated cos/sin table
+ * for positions 0..max_positions-1 (device allocation; freed by laps_ctx_destroy). */
+int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions, laps_ctx** out);
+void laps_ctx_destroy(laps_ctx* ctx);
+/* Bytes of scratch laps_prefill_layer / laps_prefill_stack need for up to max_tokens rows
+ * (padded rows count) and max_seqs sequences.  0 on bad arguments. */
+size_t laps_workspace_bytes(const laps_ctx* ctx, int32_t max_tokens, int32_t max_seqs);
+
+/* Interleaves gate and up projection rows in blocks of 32 so that one GEMM produces both
+ * halves of the SwiGLU for the same output column in one tile: dst rows [64b, 64b+32) are
+ * gate rows [32b, 32b+32), dst rows [64b+32, 64b+64) are up rows [32b, 32b+32).
+ * w_gate_dev, w_up_dev: bf16 [intermediate, hidden]; dst_dev: bf16 [2*intermediate, hidden]. */
+int laps_pack_gate_up(laps_ctx* ctx, const void* w_gate_dev, const void* w_up_dev, void* dst_dev, void* stream);
+
+/* Token-major K/V <-> paged pools.  Sequence s owns rows cu_dev[s]..cu_dev[s+1]-1 of the packed
+ * arrays ([n_tokens, n_kv_heads, head_dim] bf16), which map to its logical positions
+ * start_pos_dev[s], start_pos_dev[s]+1, ...  page_table_dev: int32 [n_seq, max_pages]. */
+int laps_kv_scatter(laps_ctx* ctx, int32_t n_seq, int32_t n_tokens, const int32_t* cu_dev,
+                    const int32_t* start_pos_dev, const int32_t* page_table_dev, int32_t max_pages,
+                    const void* k_src_dev, const void* v_src_dev, void* k_pool_dev, void* v_pool_dev, void* stream);
+int laps_kv_gather(laps_ctx* ctx, int32_t n_seq, int32_t n_tokens, const int32_t* cu_dev,
+                   const int32_t* start_pos_dev, const int32_t* page_table_dev, int32_t max_pages,
+                   const void* k_pool_dev, const void* v_pool_dev, void* k_dst_dev, void* v_dst_dev, void* stream);
+
+/* ------------------------------------------------------------------ prefill forward
+ * One decoder layer over a packed ragged batch (Section 2.1: L new tokens attending to H cached
+ * ones; Section 3.2: the "standard prefill kernel" that un-captured batches and long chunks use).
+ *   n_seq sequences, n_tokens rows.  Sequence s owns rows cu_seqlens_dev[s] .. cu_seqlens_dev[s+1]-1;
+ *   seq_len_dev (nullable) gives how many of those rows are real tokens (the rest are padding and
+ *   are ignored: no KV write, output undefined); NULL means all of them.
+ *   prefix_len_dev[s] = H_s cached tokens; page_table_dev[s][0..ceil((H_s+L_s)/16)) must be valid
+ *   pages of this layer's pools.  The layer reads the prefix from the pools and appends the new
+ *   tokens' K and V at logical positions H_s .. H_s+L_s-1 (possibly starting mid-page).
+ *   x_in_dev / x_out_dev: fp32 [n_tokens, hidden]; may alias each other.
+ *   workspace_dev: >= laps_workspace_bytes(ctx, n_tokens, n_seq) bytes, 256-byte aligned.
+ * Errors: EINVAL on NULL / non-positive sizes; ENOMEM if the workspace is too small; EHIP. */
+int laps_prefill_layer(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                       const int32_t* cu_seqlens_dev, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
+                       const int32_t* page_table_dev, int32_t max_pages, void* k_pool_dev, void* v_pool_dev,
+                       const float* x_in_dev, float* x_out_dev, void* workspace_dev, size_t workspace_bytes,
+                       void* stream);
+
+/* cfg.n_layers layers in sequence.  w: host array [n_layers]; k_pools / v_pools: host arrays
+ * [n_layers] of device pool pointers (one pool pair per layer, same page table for all layers). */
+int laps_prefill_stack(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                       const int32_t* cu_seqlens_dev, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
+                       const int32_t* page_table_dev, int32_t max_pages, void* const* k_pools, void* const* v_pools,
+                       const float* x_in_dev, float* x_out_dev, void* workspace_dev, size_t workspace_bytes,
+                       void* stream);
+
+/* ------------------------------------------------------------------ captured short buckets
+ * Section 3.1: one graph per (length bucket L_b, depth B_d) with fixed operator topology and
+ * variable memory contents.  The graph runs the whole stack on a padded [depth*len_bucket, hidden]
+ * batch whose lengths, prefix lengths and page table live in staging buffers the graph owns, so a
+ * replay needs no node updates.  Slot b owns rows b*len_bucket .. (b+1)*len_bucket-1.
+ * laps_graph_capture allocates the staging buffers and workspace, runs one warm-up pass on the
+ * stream with all slots empty, captures and instantiates.  It synchronises the stream. */
+int laps_graph_capture(laps_ctx* ctx, const laps_layer_weights* w, int32_t len_bucket, int32_t depth,
+                       int32_t max_pages, void* const* k_pools, void* const* v_pools, void* stream,
+                       laps_graph** out);
+/* Fills slots 0..n_real-1 (n_real <= depth; remaining slots become empty).  All pointers are
+ * device pointers: seq_len_dev, prefix_len_dev [n_real]; page_table_dev [n_real, max_pages] with
+ * row stride max_pages; x_rows_dev fp32 [n_real*len_bucket, hidden] already laid out slot by slot
+ * (rows beyond a slot's seq_len may hold anything finite).  Enqueues device-to-device copies. */
+int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
+                     const int32_t* page_table_dev, const float* x_rows_dev, void* stream);
+int laps_graph_replay(laps_graph* g, void* stream);
+/* Device pointer to the graph's output rows, fp32 [depth*len_bucket, hidden], valid until destroy. */
+const float* laps_graph_output(const laps_graph* g);
+/* Device pointer to the graph's input rows (same shape) for callers that write inputs in place. */
+float* laps_graph_input(laps_graph* g);
+/* Enqueues a device-to-device copy of output rows [0, n_rows) into dst_dev (fp32 [n_rows, hidden]). */
+int laps_graph_read_output(const laps_graph* g, int32_t n_rows, float* dst_dev, void* stream);
+size_t laps_graph_device_bytes(const laps_graph* g); /* staging + workspace held by this graph */
+void laps_graph_destroy(laps_graph* g);
+
+/* ------------------------------------------------------------------ single kernels (tests, roofline)
+ * C[M,N] (fp32, row-major) = A[M,K] (bf16 row-major) * W[N,K]^T (bf16 row-major).  K % 64 == 0,
+ * N % 128 == 0.  `split_k` 0 = automatic choice of the number of K slices.  workspace_dev must hold
+ * laps_gemm_workspace_bytes(m, n, k, split_k) bytes (0 when a single slice is used; then it may be NULL). */
+size_t laps_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t split_k);
+int laps_gemm_bf16(laps_ctx* ctx, const void* a_dev, const void* w_dev, float* c_dev, int32_t m, int32_t n,
+                   int32_t k, int32_t split_k, void* workspace_dev, size_t workspace_bytes, void* stream);
+/* Ragged paged causal GQA attention alone: q_dev bf16 [n_tokens, n_q*hd] (already rotated), K/V of
+ * prefix and new tokens already in the pools; out_dev bf16 [n_tokens, n_q*hd]; workspace as for
+ * laps_prefill_layer. */
+int laps_attention(laps_ctx* ctx, int32_t n_seq, int32_t n_tokens, const int32_t* cu_seqlens_dev,
+                   const int32_t* seq_len_dev, const int32_t* prefix_len_dev, const int32_t* page_table_dev,
+                   int32_t max_pages, const void* k_pool_dev, const void* v_pool_dev, const void* q_dev,
+                   void* out_dev, void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ per-kernel timing
+ * When enabled, un-captured laps_prefill_* calls bracket every kernel launch with HIP events on
+ * the caller's stream.  laps_prof_read synchronises those events and returns, per kernel class,
+ * the summed milliseconds and the launch count since the last laps_prof_enable(ctx, 1). */
+enum { LAPS_K_PREP = 0, LAPS_K_RMSNORM, LAPS_K_GEMM_QKV, LAPS_K_GEMM_O, LAPS_K_GEMM_GATEUP, LAPS_K_GEMM_DOWN,
+       LAPS_K_EPI_QKV, LAPS_K_EPI_RESID, LAPS_K_EPI_SWIGLU, LAPS_K_ATTN, LAPS_K_COUNT };
+int laps_prof_enable(laps_ctx* ctx, int32_t on);
+int laps_prof_read(laps_ctx* ctx, double* ms_out /*[LAPS_K_COUNT]*/, int64_t* count_out /*[LAPS_K_COUNT]*/);
+
+const char* laps_last_error(void);
+const char* laps_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAPS_H */

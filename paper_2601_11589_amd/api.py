@@ -1,0 +1,315 @@
+"""Thin ctypes binding over liblaps.so: same names as include/laps.h, argument marshalling only.
+
+PyTorch is used for device memory (tensors -> raw pointers) and streams; every step of the
+path runs inside the library's HIP kernels.  There is no CPU or eager fallback: if the shared
+library is missing or fails to load, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblaps.so")
+
+K_NAMES = ["prep", "rmsnorm", "gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "epi_qkv", "epi_resid",
+           "epi_swiglu", "attn"]
+
+
+class LapsError(RuntimeError):
+    pass
+
+
+class _ModelCfg(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("intermediate", C.c_int32), ("n_layers", C.c_int32), ("page_size", C.c_int32),
+                ("has_qkv_bias", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("ln1_w", "w_qkv", "b_qkv", "w_o", "ln2_w", "w_gate_up", "w_down")]
+
+
+class _PlanParams(C.Structure):
+    _fields_ = [("short_max_len", C.c_int32), ("n_len_buckets", C.c_int32), ("len_buckets", C.POINTER(C.c_int32)),
+                ("n_depths", C.c_int32), ("depths", C.POINTER(C.c_int32)), ("token_budget", C.c_int32),
+                ("long_chunk", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads liblaps.so (built in-tree by paper_2601_11589_amd.build).  Fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise LapsError(f"{LIB_PATH} not found: run `python -m paper_2601_11589_amd.build` (no fallback path exists)")
+        L = C.CDLL(LIB_PATH)
+        L.laps_last_error.restype = C.c_char_p
+        L.laps_version.restype = C.c_char_p
+        L.laps_workspace_bytes.restype = C.c_size_t
+        L.laps_gemm_workspace_bytes.restype = C.c_size_t
+        L.laps_graph_device_bytes.restype = C.c_size_t
+        L.laps_graph_output.restype = C.c_void_p
+        L.laps_graph_input.restype = C.c_void_p
+        for name in ("req_class", "req_bucket", "req_batch", "req_row", "batch_len_bucket", "batch_depth",
+                     "batch_graph_ok", "batch_req_offset", "batch_req_ids", "long_req", "long_chunk_offset",
+                     "long_chunk_len"):
+            getattr(L, "laps_plan_" + name).restype = C.POINTER(C.c_int32)
+            getattr(L, "laps_plan_" + name).argtypes = [C.c_void_p]
+        for name in ("n_requests", "n_batches", "n_long"):
+            getattr(L, "laps_plan_" + name).argtypes = [C.c_void_p]
+        L.laps_plan_free.argtypes = [C.c_void_p]
+        L.laps_ctx_destroy.argtypes = [C.c_void_p]
+        L.laps_graph_destroy.argtypes = [C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise LapsError(f"liblaps error {rc}: {lib().laps_last_error().decode()}")
+
+
+def _p(t):
+    """Raw device (or host) address of a tensor, None -> NULL."""
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+# --------------------------------------------------------------------------- plan
+def laps_plan_buckets(short_max_len, len_buckets, depths, token_budget, long_chunk, new_len, prefix_len) -> dict:
+    """Returns the plan as plain Python lists in the same structure the brute-force oracle uses."""
+    L = lib()
+    lb, lbp = _i32(len_buckets)
+    dp, dpp = _i32(depths)
+    nl, nlp = _i32(new_len)
+    pl, plp = _i32(prefix_len)
+    params = _PlanParams(short_max_len, len(lb), lbp, len(dp), dpp, token_budget, long_chunk)
+    h = C.c_void_p()
+    _check(L.laps_plan_buckets(C.byref(params), C.c_int32(len(nl)), nlp, plp, C.byref(h)))
+    try:
+        n, nb, nlong = L.laps_plan_n_requests(h), L.laps_plan_n_batches(h), L.laps_plan_n_long(h)
+
+        def arr(name, cnt):
+            ptr = getattr(L, "laps_plan_" + name)(h)
+            return [int(ptr[i]) for i in range(cnt)]
+
+        off = arr("batch_req_offset", nb + 1)
+        ids = arr("batch_req_ids", off[-1] if nb else 0)
+        lbk, dep, ok = arr("batch_len_bucket", nb), arr("batch_depth", nb), arr("batch_graph_ok", nb)
+        batches = [{"len_bucket": lbk[b], "depth": dep[b], "graph_ok": ok[b], "req_ids": ids[off[b]:off[b + 1]]}
+                   for b in range(nb)]
+        coff = arr("long_chunk_offset", nlong + 1)
+        clen = arr("long_chunk_len", coff[-1] if nlong else 0)
+        lreq = arr("long_req", nlong)
+        longs = [{"req_id": lreq[i], "chunks": clen[coff[i]:coff[i + 1]]} for i in range(nlong)]
+        return {"cls": arr("req_class", n), "bucket": arr("req_bucket", n), "batches": batches, "longs": longs,
+                "req_batch": arr("req_batch", n), "req_row": arr("req_row", n)}
+    finally:
+        L.laps_plan_free(h)
+
+
+# --------------------------------------------------------------------------- context
+def bf16_tensor(bits: np.ndarray, device="cuda") -> torch.Tensor:
+    """uint16 bf16 bit patterns (host) -> torch.bfloat16 tensor on the device."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class LapsCtx:
+    def __init__(self, cfg, max_positions: int, has_qkv_bias: bool = False):
+        self.cfg = cfg
+        self._c = _ModelCfg(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.intermediate, cfg.n_layers,
+                            cfg.page_size, int(has_qkv_bias), cfg.rope_theta, cfg.rms_eps)
+        self._h = C.c_void_p()
+        _check(lib().laps_ctx_create(C.byref(self._c), C.c_int32(max_positions), C.byref(self._h)))
+        self._ws = None
+
+    def close(self):
+        if self._h:
+            lib().laps_ctx_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- scratch
+    def laps_workspace_bytes(self, max_tokens: int, max_seqs: int) -> int:
+        return int(lib().laps_workspace_bytes(self._h, C.c_int32(max_tokens), C.c_int32(max_seqs)))
+
+    def workspace(self, max_tokens: int, max_seqs: int) -> torch.Tensor:
+        need = self.laps_workspace_bytes(max_tokens, max_seqs)
+        if need == 0:
+            raise LapsError("laps_workspace_bytes returned 0 (bad arguments)")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    # ---- weights
+    def laps_pack_gate_up(self, w_gate: torch.Tensor, w_up: torch.Tensor, stream=None) -> torch.Tensor:
+        dst = torch.empty((2 * self.cfg.intermediate, self.cfg.hidden), dtype=torch.bfloat16, device=w_gate.device)
+        _check(lib().laps_pack_gate_up(self._h, _p(w_gate), _p(w_up), _p(dst), _stream(stream)))
+        return dst
+
+    def upload_layer(self, w: dict) -> dict:
+        """Host bf16 bit arrays (inputs.make_layer_weights) -> device tensors + the packed gate/up matrix."""
+        dev = {k: bf16_tensor(v) for k, v in w.items()}
+        dev["w_gate_up"] = self.laps_pack_gate_up(dev.pop("w_gate"), dev.pop("w_up"))
+        torch.cuda.synchronize()
+        return dev
+
+    def _weights_array(self, layers):
+        arr = (_LayerWeights * len(layers))()
+        for i, w in enumerate(layers):
+            b = w.get("b_qkv")
+            arr[i] = _LayerWeights(w["ln1"].data_ptr(), w["w_qkv"].data_ptr(), b.data_ptr() if b is not None else 0,
+                                   w["w_o"].data_ptr(), w["ln2"].data_ptr(), w["w_gate_up"].data_ptr(),
+                                   w["w_down"].data_ptr())
+        return arr
+
+    # ---- KV pools
+    def new_pools(self, n_pages: int, n_layers: int | None = None, zero: bool = False):
+        n_layers = n_layers or self.cfg.n_layers
+        mk = torch.zeros if zero else torch.empty
+        shape_k = (n_pages, self.cfg.n_kv_heads, 16, self.cfg.head_dim)
+        shape_v = (n_pages, self.cfg.n_kv_heads, self.cfg.head_dim, 16)
+        return ([mk(shape_k, dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)],
+                [mk(shape_v, dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)])
+
+    def laps_kv_scatter(self, cu, start_pos, page_table, k_src, v_src, k_pool, v_pool, stream=None):
+        n_seq, n_tok = cu.numel() - 1, k_src.shape[0]
+        _check(lib().laps_kv_scatter(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(start_pos), _p(page_table),
+                                     C.c_int32(page_table.shape[1]), _p(k_src), _p(v_src), _p(k_pool), _p(v_pool),
+                                     _stream(stream)))
+
+    def laps_kv_gather(self, cu, start_pos, page_table, k_pool, v_pool, n_tokens, stream=None):
+        n_seq = cu.numel() - 1
+        shp = (n_tokens, self.cfg.n_kv_heads, self.cfg.head_dim)
+        k = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+        v = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+        _check(lib().laps_kv_gather(self._h, C.c_int32(n_seq), C.c_int32(n_tokens), _p(cu), _p(start_pos), _p(page_table),
+                                    C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(k), _p(v), _stream(stream)))
+        return k, v
+
+    # ---- forward
+    def laps_prefill_layer(self, w: dict, cu, seq_len, prefix_len, page_table, k_pool, v_pool, x_in, x_out=None,
+                           stream=None):
+        n_seq, n_tok = cu.numel() - 1, x_in.shape[0]
+        x_out = torch.empty_like(x_in) if x_out is None else x_out
+        ws = self.workspace(n_tok, n_seq)
+        arr = self._weights_array([w])
+        _check(lib().laps_prefill_layer(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
+                                        _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(x_in),
+                                        _p(x_out), _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
+        return x_out
+
+    def laps_prefill_stack(self, layers, cu, seq_len, prefix_len, page_table, k_pools, v_pools, x_in, x_out=None,
+                           stream=None):
+        n_seq, n_tok = cu.numel() - 1, x_in.shape[0]
+        x_out = torch.empty_like(x_in) if x_out is None else x_out
+        ws = self.workspace(n_tok, n_seq)
+        arr = self._weights_array(layers)
+        kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
+        vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
+        _check(lib().laps_prefill_stack(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
+                                        _p(page_table), C.c_int32(page_table.shape[1]), kp, vp, _p(x_in), _p(x_out), _p(ws),
+                                        C.c_size_t(ws.numel()), _stream(stream)))
+        return x_out
+
+    # ---- single kernels
+    def laps_gemm_bf16(self, a, w, split_k: int = 0, stream=None):
+        m, k = a.shape
+        n = w.shape[0]
+        out = torch.empty((m, n), dtype=torch.float32, device=a.device)
+        need = int(lib().laps_gemm_workspace_bytes(C.c_int32(m), C.c_int32(n), C.c_int32(k), C.c_int32(split_k)))
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=a.device)
+        _check(lib().laps_gemm_bf16(self._h, _p(a), _p(w), _p(out), C.c_int32(m), C.c_int32(n), C.c_int32(k),
+                                    C.c_int32(split_k), _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
+        return out
+
+    def laps_attention(self, cu, seq_len, prefix_len, page_table, k_pool, v_pool, q, stream=None):
+        n_seq, n_tok = cu.numel() - 1, q.shape[0]
+        out = torch.zeros_like(q)
+        ws = self.workspace(n_tok, n_seq)
+        _check(lib().laps_attention(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
+                                    _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(q), _p(out),
+                                    _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
+        return out
+
+    # ---- timing
+    def laps_prof_enable(self, on: bool):
+        _check(lib().laps_prof_enable(self._h, C.c_int32(int(on))))
+
+    def laps_prof_read(self) -> dict:
+        ms = (C.c_double * len(K_NAMES))()
+        cnt = (C.c_int64 * len(K_NAMES))()
+        _check(lib().laps_prof_read(self._h, ms, cnt))
+        return {K_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(len(K_NAMES))}
+
+    # ---- graphs
+    def laps_graph_capture(self, layers, len_bucket: int, depth: int, max_pages: int, k_pools, v_pools, stream):
+        return LapsGraph(self, layers, len_bucket, depth, max_pages, k_pools, v_pools, stream)
+
+
+class LapsGraph:
+    """One captured (length bucket, depth) shape of the whole stack."""
+
+    def __init__(self, ctx: LapsCtx, layers, len_bucket, depth, max_pages, k_pools, v_pools, stream):
+        self.ctx, self.len_bucket, self.depth, self.max_pages = ctx, len_bucket, depth, max_pages
+        self._keep = (layers, k_pools, v_pools)  # the graph holds raw pointers into these
+        arr = ctx._weights_array(layers)
+        kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
+        vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
+        self._h = C.c_void_p()
+        _check(lib().laps_graph_capture(ctx._h, arr, C.c_int32(len_bucket), C.c_int32(depth), C.c_int32(max_pages), kp, vp,
+                                        C.c_void_p(stream.cuda_stream), C.byref(self._h)))
+
+    def laps_graph_stage(self, n_real, seq_len, prefix_len, page_table, x_rows, stream=None):
+        assert page_table is None or page_table.shape[1] == self.max_pages
+        _check(lib().laps_graph_stage(self._h, C.c_int32(n_real), _p(seq_len), _p(prefix_len), _p(page_table), _p(x_rows),
+                                      _stream(stream)))
+
+    def laps_graph_replay(self, stream=None):
+        _check(lib().laps_graph_replay(self._h, _stream(stream)))
+
+    def laps_graph_read_output(self, n_rows: int, dst: torch.Tensor, stream=None):
+        _check(lib().laps_graph_read_output(self._h, C.c_int32(n_rows), _p(dst), _stream(stream)))
+        return dst
+
+    def laps_graph_device_bytes(self) -> int:
+        return int(lib().laps_graph_device_bytes(self._h))
+
+    def close(self):
+        if self._h:
+            lib().laps_graph_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

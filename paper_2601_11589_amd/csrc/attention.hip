@@ -1,0 +1,317 @@
+// Ragged, paged, causal grouped-query flash attention for gfx950.
+//
+// One workgroup = one (sequence, kv head, block of query rows).  A "query row" is a (new token t,
+// query head g of the kv head's group) pair, numbered r = t*G + g, so the G query heads that share a
+// kv head are packed into the MFMA row dimension and every K/V page is fetched once for all of them.
+// The workgroup walks the sequence's pages (cached prefix first, then the new tokens, which the QKV
+// step has already appended) in tiles of 64 keys: coalesced 4 KB page reads -> registers -> LDS.
+//
+// Both products are issued transposed so that a lane owns one query row end to end:
+//   S^T = K Q^T   (A = K fragment from LDS, B = Q fragment held in registers)
+//   O^T = V^T P^T (A = V^T fragment from LDS - V pages are stored [head_dim][16 tokens], B = P)
+// With the 32x32 accumulator layout (lane -> column, registers -> rows) the softmax statistics of a
+// row live in one lane and its partner lane^32: row max and row sum need a single cross-lane
+// exchange, and the O rescale is a per-lane scalar.  K rows are read from LDS through the
+// permutation key(8a + 4h + b) = 16(a/2) + 8h + 4(a%2) + b, which makes the eight probabilities a
+// lane holds in accumulator registers 8u..8u+7 exactly the eight consecutive keys its P fragment
+// must supply to the second product - no shuffles between the two MFMA stages.
+#include "laps_internal.h"
+
+namespace {
+
+constexpr int KT = 64;      // keys per tile (4 pages)
+constexpr int NTHR = 256;   // 4 waves
+
+__device__ __forceinline__ int swz8(int row, int c) { return c ^ ((row & 7) ^ ((row >> 3) & 1)); }
+__device__ __forceinline__ int swz16(int row, int c) { return c ^ (row & 15); }
+
+// per-sequence number of query-row blocks and their exclusive prefix sum (single workgroup)
+__global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__ new_len, int n_seq, int group,
+                                                          int rows_per_wg, int* __restrict__ tile_start) {
+    __shared__ int buf[256];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_seq; base += 256) {
+        const int i = base + threadIdx.x;
+        const int v = (i < n_seq) ? (new_len[i] * group + rows_per_wg - 1) / rows_per_wg : 0;
+        buf[threadIdx.x] = v;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele scan
+            const int add = (threadIdx.x >= o) ? buf[threadIdx.x - o] : 0;
+            __syncthreads();
+            buf[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int c = carry;
+        if (i < n_seq) tile_start[i] = c + buf[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry = c + buf[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tile_start[n_seq] = carry;
+}
+
+template <int HD, int MT>
+__global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out,
+                                                     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
+                                                     const int* __restrict__ row_start, const int* __restrict__ new_len,
+                                                     const int* __restrict__ prefix_len, const int* __restrict__ page_table,
+                                                     int max_pages, const int* __restrict__ tile_start, int n_seq,
+                                                     int n_q, int n_kv, float scale_log2e) {
+    constexpr int CPR = HD / 8;            // 16-byte chunks per K row
+    constexpr int CPP = HD * 2;            // 16-byte chunks per page (K and V alike)
+    constexpr int NLD = KT * CPR / NTHR;   // chunk loads per thread per tile, K and V each
+    constexpr int KSTEPS = HD / 16;        // MFMA k-steps over head_dim
+    constexpr int NI = HD / 32;            // output sub-tiles over head_dim
+    constexpr int ROWS = 128 * MT;
+
+    __shared__ __align__(16) u32x4 Ks[KT * CPR];
+    __shared__ __align__(16) u32x4 Vs[HD * 8];
+
+    const int item = blockIdx.x;
+    if (item >= tile_start[n_seq]) return;
+    int lo = 0, hi = n_seq;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_start[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int seq = lo;
+    const int qtile = item - tile_start[seq];
+    const int kvh = blockIdx.y;
+    const int G = n_q / n_kv;
+    const int L = new_len[seq], H = prefix_len[seq];
+    const int n_rows = L * G;
+    const int kv_len = H + L;
+    const int n_pages_seq = (kv_len + LAPS_PAGE - 1) / LAPS_PAGE;
+    const int R0 = qtile * ROWS;
+    if (R0 >= n_rows) return;
+    const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
+    const int kv_end = H + last_row_wg / G + 1;  // keys visible to the last row of this block
+    const int* pt = page_table + (size_t)seq * max_pages;
+    const size_t tok0 = (size_t)row_start[seq];
+    const int q_stride = n_q * HD;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lm = lane & 31, lh = lane >> 5;
+
+    // ---- Q fragments (registers for the whole kernel) and per-row causal limits
+    bf16x8 qf[MT][KSTEPS];
+    int limit[MT];      // last visible key of this lane's row
+    int row_id[MT];     // unclamped row index
+    int vis_max = 0;    // wave-uniform: last key any row of this wave sees
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int base = R0 + (mt * 4 + wave) * 32;
+        const int r = base + lm;
+        row_id[mt] = r;
+        const int rc = r < n_rows ? r : n_rows - 1;
+        const int t = rc / G, g = rc - t * G;
+        limit[mt] = H + t;
+        const int last = (base + 31 < n_rows ? base + 31 : n_rows - 1);
+        const int vm = (base < n_rows) ? H + last / G : -1;
+        vis_max = vm > vis_max ? vm : vis_max;
+        const u32x4* qp = reinterpret_cast<const u32x4*>(q + (tok0 + t) * q_stride + (size_t)(kvh * G + g) * HD);
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) qf[mt][kk] = __builtin_bit_cast(bf16x8, qp[kk * 2 + lh]);
+    }
+
+    f32x16 o[MT][NI];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY;
+        l_run[mt] = 0.f;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[mt][ni][i] = 0.f;
+    }
+
+    // ---- tile copy assignment: chunk c = tid + i*NTHR of the tile's 4 pages
+    u32x4 kreg[NLD], vreg[NLD];
+    auto load_tile = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int c = tid + i * NTHR;
+            const int pi = c / CPP, within = c % CPP;
+            int pidx = j0 / LAPS_PAGE + pi;
+            pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
+            const size_t page = (size_t)pt[pidx];
+            const size_t off = ((page * n_kv + kvh) * CPP + within);
+            kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
+            vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];
+        }
+    };
+    auto store_tile = [&](int j0) {
+        const bool tail = (j0 + KT > kv_len);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int c = tid + i * NTHR;
+            const int pi = c / CPP, within = c % CPP;
+            {   // K page is [16 keys][HD]
+                const int key = pi * LAPS_PAGE + within / CPR, kc = within % CPR;
+                Ks[key * CPR + (CPR == 16 ? swz16(key, kc) : swz8(key, kc))] = kreg[i];
+            }
+            {   // V page is [HD][16 keys]: chunk = 8 consecutive keys of one head_dim index
+                const int e = within / 2, half = within & 1;
+                u32x4 v = vreg[i];
+                if (tail) {  // zero keys >= kv_len so that 0 * garbage cannot produce NaN
+                    const int nvalid = kv_len - (j0 + pi * LAPS_PAGE + half * 8);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        unsigned x = v[w];
+                        if (2 * w + 1 >= nvalid) x &= 0x0000ffffu;
+                        if (2 * w >= nvalid) x = 0u;
+                        v[w] = x;
+                    }
+                }
+                Vs[e * 8 + swz8(e, pi * 2 + half)] = v;
+            }
+        }
+    };
+
+    load_tile(0);
+    for (int j0 = 0; j0 < kv_end; j0 += KT) {
+        __syncthreads();
+        store_tile(j0);
+        __syncthreads();
+        if (j0 + KT < kv_end) load_tile(j0 + KT);
+        if (j0 > vis_max) continue;  // wave-uniform: nothing of this tile is visible to this wave
+
+        // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key sub-tiles)
+        f32x16 s[MT][2];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[mt][sub][i] = 0.f;
+        // MFMA row rho = lm holds key 16(a/2) + 8h + 4(a%2) + b with rho = 8a + 4h + b
+        const int ra = lm >> 3, rh = (lm >> 2) & 1, rb = lm & 3;
+        const int krow = 16 * (ra >> 1) + 8 * rh + 4 * (ra & 1) + rb;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int row = sub * 32 + krow;
+                const int ch = kk * 2 + lh;
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, Ks[row * CPR + (CPR == 16 ? swz16(row, ch) : swz8(row, ch))]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    s[mt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mt][kk], s[mt][sub], 0, 0, 0);
+            }
+        }
+
+        // ---- causal mask + online softmax, one query row per lane (shared with lane ^ 32)
+        bf16x8 pf[MT][2][2];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int a = i >> 2, b = i & 3;
+                    const int key = j0 + sub * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
+                    const float v = (key <= limit[mt]) ? s[mt][sub][i] * scale_log2e : -INFINITY;
+                    s[mt][sub][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[mt], mx);           // finite from the first tile on (key 0 is visible)
+            const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);
+            m_run[mt] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    bf16x8 pk;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float p = __builtin_amdgcn_exp2f(s[mt][sub][8 * u + e] - m_new);
+                        psum += p;
+                        pk[e] = (__bf16)p;
+                    }
+                    pf[mt][sub][u] = pk;
+                }
+            l_run[mt] = l_run[mt] * alpha + psum;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mt][ni][i] *= alpha;
+        }
+
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int u2 = 0; u2 < 4; ++u2) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int row = ni * 32 + lm;
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, Vs[row * 8 + swz8(row, u2 * 2 + lh)]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    o[mt][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mt][u2 >> 1][u2 & 1], o[mt][ni], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- normalise and store: lane owns row r; register i of sub-tile ni is head_dim index
+    //      ni*32 + 8*(i/4) + 4*(lane/32) + i%4
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const float l_tot = l_run[mt] + __shfl_xor(l_run[mt], 32, 64);
+        const int r = row_id[mt];
+        if (r >= n_rows) continue;
+        const float inv = 1.f / l_tot;
+        const int t = r / G, g = r - t * G;
+        bf16_t* op = out + (tok0 + t) * q_stride + (size_t)(kvh * G + g) * HD;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                u32x2 w;
+                w.x = pack_bf16x2(o[mt][ni][4 * a] * inv, o[mt][ni][4 * a + 1] * inv);
+                w.y = pack_bf16x2(o[mt][ni][4 * a + 2] * inv, o[mt][ni][4 * a + 3] * inv);
+                *reinterpret_cast<u32x2*>(op + ni * 32 + 8 * a + 4 * lh) = w;
+            }
+    }
+}
+
+template <int HD, int MT>
+int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool, const int* row_start,
+                const int* new_len, const int* prefix_len, const int* page_table, int max_pages, const int* tile_start,
+                int n_seq, int max_items, int n_q, int n_kv, hipStream_t s) {
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+    hipLaunchKernelGGL((attn_kernel<HD, MT>), dim3(max_items, n_kv), dim3(NTHR), 0, s, q, out, k_pool, v_pool, row_start,
+                       new_len, prefix_len, page_table, max_pages, tile_start, n_seq, n_q, n_kv, scale_log2e);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+}  // namespace
+
+int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
+                          const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
+                          int max_pages, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv, int hd,
+                          hipStream_t s) {
+    const int group = n_q / n_kv;
+    const long total_rows = (long)n_tokens * group;
+    const int mt = (total_rows > 128L * n_seq) ? 2 : 1;  // average rows per sequence above one 128-row block
+    const int rows_per_wg = 128 * mt;
+    // every sequence contributes ceil(rows/rows_per_wg) blocks: at most rows/rows_per_wg + 1
+    const int max_items = (int)(total_rows / rows_per_wg) + n_seq;
+    hipLaunchKernelGGL(attn_sched_kernel, dim3(1), dim3(256), 0, s, new_len, n_seq, group, rows_per_wg, tile_start);
+    LAPS_LAUNCH_CHECK();
+    if (hd == 128) {
+        if (mt == 2) return launch_attn<128, 2>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<128, 1>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+    }
+    if (hd == 64) {
+        if (mt == 2) return launch_attn<64, 2>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<64, 1>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+    }
+    laps_set_error("attention: head_dim %d not supported (64 or 128)", hd);
+    return LAPS_EINVAL;
+}

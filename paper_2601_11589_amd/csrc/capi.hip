@@ -1,0 +1,611 @@
+// C ABI of liblaps: context, workspace carving, the layer / stack driver, captured short-bucket
+// graphs, per-kernel event timing.  Every device step is a kernel from gemm.hip, elementwise.hip or
+// attention.hip; this file only sequences launches on the caller's stream.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "laps_internal.h"
+
+// ----------------------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+
+void laps_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+extern "C" const char* laps_last_error(void) { return g_err; }
+extern "C" const char* laps_version(void) { return "laps-gfx950 0.1"; }
+
+// ----------------------------------------------------------------------------- context
+struct laps_ctx {
+    laps_model_cfg cfg;
+    int device;
+    int max_pos;
+    float2* rope;  // [max_pos][hd/2] (cos, sin)
+    // timing
+    bool prof_on;
+    std::vector<hipEvent_t> ev;  // pairs (start, stop)
+    std::vector<int> ev_class;
+    size_t ev_used;
+};
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+    size_t tok_pos, tok_slot, new_len, tile_start, r, q, attn, act, x_mid, partial, total;
+};
+
+static size_t partial_bytes_for(const laps_model_cfg& c, int m) {
+    const int qd = c.n_q_heads * c.head_dim, qkv = qd + 2 * c.n_kv_heads * c.head_dim;
+    size_t b = laps_gemm_partial_bytes(m, qkv, c.hidden);
+    size_t t = laps_gemm_partial_bytes(m, c.hidden, qd);
+    b = t > b ? t : b;
+    t = laps_gemm_partial_bytes(m, 2 * c.intermediate, c.hidden);
+    b = t > b ? t : b;
+    t = laps_gemm_partial_bytes(m, c.hidden, c.intermediate);
+    return t > b ? t : b;
+}
+
+static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs) {
+    WsLayout w;
+    const size_t M = (size_t)max_tokens;
+    const int qd = c.n_q_heads * c.head_dim;
+    size_t o = 0;
+    w.tok_pos = o;    o += align256(M * 4);
+    w.tok_slot = o;   o += align256(M * 4);
+    w.new_len = o;    o += align256((size_t)max_seqs * 4);
+    w.tile_start = o; o += align256((size_t)(max_seqs + 1) * 4);
+    w.r = o;          o += align256(M * c.hidden * 2);
+    w.q = o;          o += align256(M * qd * 2);
+    w.attn = o;       o += align256(M * qd * 2);
+    w.act = o;        o += align256(M * c.intermediate * 2);
+    w.x_mid = o;      o += align256(M * c.hidden * 4);
+    // split-K partial sums: the split factor depends on the number of row tiles, and the byte count
+    // grows with m inside one row-tile count, so the maximum over m <= max_tokens is reached at a
+    // row-tile boundary (or at max_tokens, or at the largest skinny m = 128).
+    size_t pb = partial_bytes_for(c, max_tokens);
+    if (max_tokens > 128) {
+        const size_t t = partial_bytes_for(c, 128);
+        pb = t > pb ? t : pb;
+    }
+    for (int m = 256; m < max_tokens; m += 256) {
+        const size_t t = partial_bytes_for(c, m);
+        pb = t > pb ? t : pb;
+    }
+    w.partial = o;    o += align256(pb);
+    w.total = o;
+    return w;
+}
+
+static int check_cfg(const laps_model_cfg* c) {
+    if (!c) return 0;
+    const int qd = c->n_q_heads * c->head_dim, qkv = qd + 2 * c->n_kv_heads * c->head_dim;
+    if (c->head_dim != 64 && c->head_dim != 128) return 0;
+    if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return 0;
+    if (c->hidden < 128 || c->hidden % 128 || qd % 64 || c->intermediate < 64 || c->intermediate % 64) return 0;
+    if (qkv % 128 || (2 * c->intermediate) % 128) return 0;
+    if (c->hidden > 8192) return 0;
+    if (c->page_size != LAPS_PAGE || c->n_layers < 1) return 0;
+    if (!(c->rope_theta > 0.f) || !(c->rms_eps > 0.f)) return 0;
+    return 1;
+}
+
+extern "C" int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions, laps_ctx** out) {
+    if (!out || !check_cfg(cfg) || max_positions < 1) {
+        laps_set_error("ctx_create: unsupported model shape or max_positions < 1");
+        return LAPS_EINVAL;
+    }
+    laps_ctx* c = new (std::nothrow) laps_ctx();
+    if (!c) {
+        laps_set_error("ctx_create: out of host memory");
+        return LAPS_ENOMEM;
+    }
+    c->cfg = *cfg;
+    c->max_pos = max_positions;
+    c->rope = nullptr;
+    c->prof_on = false;
+    c->ev_used = 0;
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipMalloc(&c->rope, (size_t)max_positions * (cfg->head_dim / 2) * sizeof(float2));
+    if (e != hipSuccess) {
+        laps_set_error("ctx_create: %s", hipGetErrorString(e));
+        delete c;
+        return e == hipErrorOutOfMemory ? LAPS_ENOMEM : LAPS_EHIP;
+    }
+    int rc = laps_launch_rope_table(c->rope, max_positions, cfg->head_dim, cfg->rope_theta, nullptr);
+    if (rc == LAPS_OK && hipDeviceSynchronize() != hipSuccess) {
+        laps_set_error("ctx_create: rope table kernel failed");
+        rc = LAPS_EHIP;
+    }
+    if (rc != LAPS_OK) {
+        (void)hipFree(c->rope);
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return LAPS_OK;
+}
+
+extern "C" void laps_ctx_destroy(laps_ctx* c) {
+    if (!c) return;
+    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    if (c->rope) (void)hipFree(c->rope);
+    delete c;
+}
+
+extern "C" size_t laps_workspace_bytes(const laps_ctx* c, int32_t max_tokens, int32_t max_seqs) {
+    if (!c || max_tokens < 1 || max_seqs < 1) return 0;
+    return ws_layout(c->cfg, max_tokens, max_seqs).total;
+}
+
+// ----------------------------------------------------------------------------- timing
+struct ProfScope {
+    laps_ctx* c;
+    hipStream_t s;
+    bool on;
+    ProfScope(laps_ctx* ctx, hipStream_t st, int cls, bool capturing) : c(ctx), s(st), on(ctx->prof_on && !capturing) {
+        if (!on) return;
+        if (c->ev_used + 2 > c->ev.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+                on = false;
+                return;
+            }
+            c->ev.push_back(a);
+            c->ev.push_back(b);
+        }
+        c->ev_class.resize(c->ev.size() / 2);
+        c->ev_class[c->ev_used / 2] = cls;
+        (void)hipEventRecord(c->ev[c->ev_used], s);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(c->ev[c->ev_used + 1], s);
+        c->ev_used += 2;
+    }
+};
+
+extern "C" int laps_prof_enable(laps_ctx* c, int32_t on) {
+    if (!c) return LAPS_EINVAL;
+    c->prof_on = on != 0;
+    c->ev_used = 0;
+    return LAPS_OK;
+}
+
+extern "C" int laps_prof_read(laps_ctx* c, double* ms_out, int64_t* count_out) {
+    if (!c || !ms_out || !count_out) return LAPS_EINVAL;
+    for (int i = 0; i < LAPS_K_COUNT; ++i) {
+        ms_out[i] = 0.0;
+        count_out[i] = 0;
+    }
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        LAPS_HIP(hipEventSynchronize(c->ev[i + 1]));
+        float ms = 0.f;
+        LAPS_HIP(hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]));
+        const int cls = c->ev_class[i / 2];
+        ms_out[cls] += ms;
+        count_out[cls] += 1;
+    }
+    c->ev_used = 0;
+    return LAPS_OK;
+}
+
+// ----------------------------------------------------------------------------- layer driver
+struct BatchDesc {
+    int n_seq, n_tokens;
+    const int *row_start, *seq_len, *prefix_len, *page_table;
+    int max_pages;
+};
+
+static int run_gemm(laps_ctx* c, int cls, bool capturing, const bf16_t* a, const bf16_t* w, float* partial, int m, int n,
+                    int k, int* split_out, hipStream_t s) {
+    const GemmPlan p = laps_gemm_plan(m, n, k, 0);
+    *split_out = p.split;
+    ProfScope ps(c, s, cls, capturing);
+    return laps_gemm_launch(p, a, w, partial, m, n, k, s);
+}
+
+#define LAPS_TRY(x)                 \
+    do {                            \
+        int rc_ = (x);              \
+        if (rc_ != LAPS_OK) return rc_; \
+    } while (0)
+
+// Runs layers [0, n_layers) of `w`.  Token metadata (prep) is computed once.
+static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, const BatchDesc& b, void* const* k_pools,
+                      void* const* v_pools, const float* x_in, float* x_out, unsigned char* ws, bool capturing,
+                      hipStream_t s) {
+    const laps_model_cfg& cf = c->cfg;
+    const int M = b.n_tokens, d = cf.hidden, hd = cf.head_dim;
+    const int qd = cf.n_q_heads * hd, qkv = qd + 2 * cf.n_kv_heads * hd, I = cf.intermediate;
+    const WsLayout L = ws_layout(cf, M, b.n_seq);
+    int* tok_pos = reinterpret_cast<int*>(ws + L.tok_pos);
+    int* tok_slot = reinterpret_cast<int*>(ws + L.tok_slot);
+    int* new_len = reinterpret_cast<int*>(ws + L.new_len);
+    int* tile_start = reinterpret_cast<int*>(ws + L.tile_start);
+    bf16_t* r = reinterpret_cast<bf16_t*>(ws + L.r);
+    bf16_t* q = reinterpret_cast<bf16_t*>(ws + L.q);
+    bf16_t* attn = reinterpret_cast<bf16_t*>(ws + L.attn);
+    bf16_t* act = reinterpret_cast<bf16_t*>(ws + L.act);
+    float* x_mid = reinterpret_cast<float*>(ws + L.x_mid);
+    float* partial = reinterpret_cast<float*>(ws + L.partial);
+
+    {
+        ProfScope ps(c, s, LAPS_K_PREP, capturing);
+        LAPS_TRY(laps_launch_prep(M, b.n_seq, b.row_start, b.seq_len, b.prefix_len, b.page_table, b.max_pages, new_len,
+                                  tok_pos, tok_slot, s));
+    }
+    {
+        ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
+        LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, s));
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const laps_layer_weights& lw = w[l];
+        const float* resid = (l == 0) ? x_in : x_out;
+        bf16_t* kp = static_cast<bf16_t*>(k_pools[l]);
+        bf16_t* vp = static_cast<bf16_t*>(v_pools[l]);
+        int split = 1;
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r, static_cast<const bf16_t*>(lw.w_qkv), partial, M, qkv, d, &split, s));
+        {
+            ProfScope ps(c, s, LAPS_K_EPI_QKV, capturing);
+            LAPS_TRY(laps_launch_epi_qkv(partial, split, cf.has_qkv_bias ? static_cast<const bf16_t*>(lw.b_qkv) : nullptr,
+                                         tok_pos, tok_slot, c->rope, c->max_pos, q, kp, vp, M, cf.n_q_heads,
+                                         cf.n_kv_heads, hd, s));
+        }
+        {
+            ProfScope ps(c, s, LAPS_K_ATTN, capturing);
+            LAPS_TRY(laps_launch_attention(q, attn, kp, vp, b.row_start, new_len, b.prefix_len, b.page_table, b.max_pages,
+                                           b.n_seq, M, tile_start, cf.n_q_heads, cf.n_kv_heads, hd, s));
+        }
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), partial, M, d, qd, &split, s));
+        {
+            ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
+            LAPS_TRY(laps_launch_epi_resid(partial, split, resid, x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d,
+                                           cf.rms_eps, s));
+        }
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_GATEUP, capturing, r, static_cast<const bf16_t*>(lw.w_gate_up), partial, M, 2 * I, d, &split, s));
+        {
+            ProfScope ps(c, s, LAPS_K_EPI_SWIGLU, capturing);
+            LAPS_TRY(laps_launch_epi_swiglu(partial, split, act, M, I, s));
+        }
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_DOWN, capturing, act, static_cast<const bf16_t*>(lw.w_down), partial, M, d, I, &split, s));
+        {
+            ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
+            const bf16_t* next_ln = (l + 1 < n_layers) ? static_cast<const bf16_t*>(w[l + 1].ln1_w) : nullptr;
+            LAPS_TRY(laps_launch_epi_resid(partial, split, x_mid, x_out, next_ln, r, M, d, cf.rms_eps, s));
+        }
+    }
+    return LAPS_OK;
+}
+
+static int check_batch_args(laps_ctx* c, const laps_layer_weights* w, int n_layers, int n_seq, int n_tokens,
+                            const void* cu, const void* prefix, const void* pt, int max_pages, const void* x_in,
+                            const void* x_out, const void* ws, size_t ws_bytes) {
+    if (!c || !w || !cu || !prefix || !pt || !x_in || !x_out || !ws || n_seq < 1 || n_tokens < 1 || max_pages < 1) {
+        laps_set_error("prefill: NULL pointer or non-positive size");
+        return LAPS_EINVAL;
+    }
+    for (int l = 0; l < n_layers; ++l)
+        if (!w[l].ln1_w || !w[l].w_qkv || !w[l].w_o || !w[l].ln2_w || !w[l].w_gate_up || !w[l].w_down ||
+            (c->cfg.has_qkv_bias && !w[l].b_qkv)) {
+            laps_set_error("prefill: layer %d has a NULL weight pointer", l);
+            return LAPS_EINVAL;
+        }
+    if (((uintptr_t)ws & 255) != 0) {
+        laps_set_error("prefill: workspace must be 256-byte aligned");
+        return LAPS_EINVAL;
+    }
+    const size_t need = ws_layout(c->cfg, n_tokens, n_seq).total;
+    if (ws_bytes < need) {
+        laps_set_error("prefill: workspace too small (%zu < %zu bytes)", ws_bytes, need);
+        return LAPS_ENOMEM;
+    }
+    return LAPS_OK;
+}
+
+extern "C" int laps_prefill_layer(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                                  const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
+                                  const int32_t* page_table, int32_t max_pages, void* k_pool, void* v_pool,
+                                  const float* x_in, float* x_out, void* ws, size_t ws_bytes, void* stream) {
+    LAPS_TRY(check_batch_args(c, w, 1, n_seq, n_tokens, cu, prefix_len, page_table, max_pages, x_in, x_out, ws, ws_bytes));
+    if (!k_pool || !v_pool) {
+        laps_set_error("prefill_layer: NULL KV pool");
+        return LAPS_EINVAL;
+    }
+    const BatchDesc b{n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages};
+    void* kp[1] = {k_pool};
+    void* vp[1] = {v_pool};
+    return run_layers(c, w, 1, b, kp, vp, x_in, x_out, static_cast<unsigned char*>(ws), false,
+                      static_cast<hipStream_t>(stream));
+}
+
+extern "C" int laps_prefill_stack(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                                  const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
+                                  const int32_t* page_table, int32_t max_pages, void* const* k_pools,
+                                  void* const* v_pools, const float* x_in, float* x_out, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    if (!c) {
+        laps_set_error("prefill_stack: NULL context");
+        return LAPS_EINVAL;
+    }
+    LAPS_TRY(check_batch_args(c, w, c->cfg.n_layers, n_seq, n_tokens, cu, prefix_len, page_table, max_pages, x_in, x_out,
+                              ws, ws_bytes));
+    if (!k_pools || !v_pools) {
+        laps_set_error("prefill_stack: NULL KV pool array");
+        return LAPS_EINVAL;
+    }
+    for (int l = 0; l < c->cfg.n_layers; ++l)
+        if (!k_pools[l] || !v_pools[l]) {
+            laps_set_error("prefill_stack: layer %d has a NULL KV pool", l);
+            return LAPS_EINVAL;
+        }
+    const BatchDesc b{n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages};
+    return run_layers(c, w, c->cfg.n_layers, b, k_pools, v_pools, x_in, x_out, static_cast<unsigned char*>(ws), false,
+                      static_cast<hipStream_t>(stream));
+}
+
+// ----------------------------------------------------------------------------- helpers
+extern "C" int laps_pack_gate_up(laps_ctx* c, const void* wg, const void* wu, void* dst, void* stream) {
+    if (!c || !wg || !wu || !dst) {
+        laps_set_error("pack_gate_up: NULL argument");
+        return LAPS_EINVAL;
+    }
+    if (c->cfg.intermediate % 32 || c->cfg.hidden % 8) {
+        laps_set_error("pack_gate_up: intermediate must be a multiple of 32");
+        return LAPS_EINVAL;
+    }
+    return laps_launch_pack_gate_up(static_cast<const bf16_t*>(wg), static_cast<const bf16_t*>(wu),
+                                    static_cast<bf16_t*>(dst), c->cfg.intermediate, c->cfg.hidden,
+                                    static_cast<hipStream_t>(stream));
+}
+
+static int kv_move(bool scatter, laps_ctx* c, int n_seq, int n_tokens, const int* cu, const int* start_pos,
+                   const int* pt, int max_pages, void* k_tok, void* v_tok, void* k_pool, void* v_pool, void* stream) {
+    if (!c || n_seq < 1 || n_tokens < 0 || !cu || !start_pos || !pt || max_pages < 1 || !k_pool || !v_pool ||
+        (n_tokens > 0 && (!k_tok || !v_tok))) {
+        laps_set_error("kv move: NULL pointer or bad size");
+        return LAPS_EINVAL;
+    }
+    return laps_launch_kv_move(scatter, n_seq, n_tokens, cu, start_pos, pt, max_pages, static_cast<bf16_t*>(k_tok),
+                               static_cast<bf16_t*>(v_tok), static_cast<bf16_t*>(k_pool), static_cast<bf16_t*>(v_pool),
+                               c->cfg.n_kv_heads, c->cfg.head_dim, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int laps_kv_scatter(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* start_pos,
+                               const int32_t* pt, int32_t max_pages, const void* k_src, const void* v_src, void* k_pool,
+                               void* v_pool, void* stream) {
+    return kv_move(true, c, n_seq, n_tokens, cu, start_pos, pt, max_pages, const_cast<void*>(k_src),
+                   const_cast<void*>(v_src), k_pool, v_pool, stream);
+}
+
+extern "C" int laps_kv_gather(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* start_pos,
+                              const int32_t* pt, int32_t max_pages, const void* k_pool, const void* v_pool, void* k_dst,
+                              void* v_dst, void* stream) {
+    return kv_move(false, c, n_seq, n_tokens, cu, start_pos, pt, max_pages, k_dst, v_dst, const_cast<void*>(k_pool),
+                   const_cast<void*>(v_pool), stream);
+}
+
+extern "C" size_t laps_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t split_k) {
+    if (m < 1 || n < 128 || n % 128 || k < 64 || k % 64 || split_k < 0) return 0;
+    const GemmPlan p = laps_gemm_plan(m, n, k, split_k);
+    return p.split == 1 ? 0 : (size_t)p.split * m * n * sizeof(float);
+}
+
+extern "C" int laps_gemm_bf16(laps_ctx* c, const void* a, const void* w, float* out, int32_t m, int32_t n, int32_t k,
+                              int32_t split_k, void* ws, size_t ws_bytes, void* stream) {
+    if (!c || !a || !w || !out || m < 1 || split_k < 0) {
+        laps_set_error("gemm: NULL pointer or bad size");
+        return LAPS_EINVAL;
+    }
+    if (n < 128 || n % 128 || k < 64 || k % 64) {
+        laps_set_error("gemm: need n %% 128 == 0 and k %% 64 == 0 (n=%d k=%d)", n, k);
+        return LAPS_EINVAL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const GemmPlan p = laps_gemm_plan(m, n, k, split_k);
+    if (p.split == 1) return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), out, m, n, k, s);
+    const size_t need = (size_t)p.split * m * n * sizeof(float);
+    if (!ws || ws_bytes < need || ((uintptr_t)ws & 255)) {
+        laps_set_error("gemm: split-K needs %zu bytes of 256-byte aligned workspace", need);
+        return LAPS_ENOMEM;
+    }
+    LAPS_TRY(laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), static_cast<float*>(ws), m, n, k, s));
+    // sum the slices: view [m, n] as rows of `cols` columns, cols | n and cols <= 8192
+    int cols = n;
+    while (cols > 8192) {
+        if (cols % 2) {
+            laps_set_error("gemm: cannot fold n=%d for the slice reducer", n);
+            return LAPS_EINVAL;
+        }
+        cols /= 2;
+    }
+    const int rows = (int)(((size_t)m * n) / cols);
+    return laps_launch_epi_resid(static_cast<const float*>(ws), p.split, nullptr, out, nullptr, nullptr, rows, cols, 1.f, s);
+}
+
+extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* seq_len,
+                              const int32_t* prefix_len, const int32_t* pt, int32_t max_pages, const void* k_pool,
+                              const void* v_pool, const void* q, void* out, void* ws, size_t ws_bytes, void* stream) {
+    if (!c || n_seq < 1 || n_tokens < 1 || !cu || !prefix_len || !pt || max_pages < 1 || !k_pool || !v_pool || !q ||
+        !out || !ws || ((uintptr_t)ws & 255)) {
+        laps_set_error("attention: NULL pointer or bad size");
+        return LAPS_EINVAL;
+    }
+    const WsLayout L = ws_layout(c->cfg, n_tokens, n_seq);
+    if (ws_bytes < L.total) {
+        laps_set_error("attention: workspace too small (%zu < %zu bytes)", ws_bytes, L.total);
+        return LAPS_ENOMEM;
+    }
+    unsigned char* w8 = static_cast<unsigned char*>(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int* new_len = reinterpret_cast<int*>(w8 + L.new_len);
+    LAPS_TRY(laps_launch_prep(n_tokens, n_seq, cu, seq_len, prefix_len, pt, max_pages, new_len,
+                              reinterpret_cast<int*>(w8 + L.tok_pos), reinterpret_cast<int*>(w8 + L.tok_slot), s));
+    return laps_launch_attention(static_cast<const bf16_t*>(q), static_cast<bf16_t*>(out),
+                                 static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), cu, new_len,
+                                 prefix_len, pt, max_pages, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),
+                                 c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.head_dim, s);
+}
+
+// ----------------------------------------------------------------------------- captured buckets
+struct laps_graph {
+    laps_ctx* ctx;
+    int len_bucket, depth, max_pages, n_layers;
+    unsigned char* block;  // one device allocation holding everything below
+    size_t block_bytes;
+    float *x_in, *x_out;
+    int *row_start, *seq_len, *prefix_len, *page_table;
+    unsigned char* ws;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int32_t len_bucket, int32_t depth,
+                                  int32_t max_pages, void* const* k_pools, void* const* v_pools, void* stream,
+                                  laps_graph** out) {
+    if (!c || !w || !out || len_bucket < 1 || depth < 1 || max_pages < 1 || !k_pools || !v_pools) {
+        laps_set_error("graph_capture: NULL pointer or non-positive size");
+        return LAPS_EINVAL;
+    }
+    const int nl = c->cfg.n_layers;
+    for (int l = 0; l < nl; ++l)
+        if (!k_pools[l] || !v_pools[l] || !w[l].ln1_w || !w[l].w_qkv || !w[l].w_o || !w[l].ln2_w || !w[l].w_gate_up ||
+            !w[l].w_down) {
+            laps_set_error("graph_capture: layer %d has a NULL pointer", l);
+            return LAPS_EINVAL;
+        }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (s == nullptr) {
+        laps_set_error("graph_capture: the null stream cannot be captured; pass a created stream");
+        return LAPS_EINVAL;
+    }
+    laps_graph* g = new (std::nothrow) laps_graph();
+    if (!g) {
+        laps_set_error("graph_capture: out of host memory");
+        return LAPS_ENOMEM;
+    }
+    memset(g, 0, sizeof(*g));
+    g->ctx = c;
+    g->len_bucket = len_bucket;
+    g->depth = depth;
+    g->max_pages = max_pages;
+    g->n_layers = nl;
+    const size_t M = (size_t)len_bucket * depth, d = c->cfg.hidden;
+    const size_t ws_bytes = ws_layout(c->cfg, (int)M, depth).total;
+    size_t o = 0;
+    const size_t o_xin = o;  o += align256(M * d * 4);
+    const size_t o_xout = o; o += align256(M * d * 4);
+    const size_t o_rs = o;   o += align256((size_t)(depth + 1) * 4);
+    const size_t o_sl = o;   o += align256((size_t)depth * 4);
+    const size_t o_pl = o;   o += align256((size_t)depth * 4);
+    const size_t o_pt = o;   o += align256((size_t)depth * max_pages * 4);
+    const size_t o_ws = o;   o += ws_bytes;
+    g->block_bytes = o;
+    auto fail = [&](int rc) {
+        if (g->exec) (void)hipGraphExecDestroy(g->exec);
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        if (g->block) (void)hipFree(g->block);
+        delete g;
+        return rc;
+    };
+    hipError_t e = hipMalloc(&g->block, g->block_bytes);
+    if (e != hipSuccess) {
+        laps_set_error("graph_capture: hipMalloc(%zu) failed: %s", g->block_bytes, hipGetErrorString(e));
+        g->block = nullptr;
+        return fail(e == hipErrorOutOfMemory ? LAPS_ENOMEM : LAPS_EHIP);
+    }
+    g->x_in = reinterpret_cast<float*>(g->block + o_xin);
+    g->x_out = reinterpret_cast<float*>(g->block + o_xout);
+    g->row_start = reinterpret_cast<int*>(g->block + o_rs);
+    g->seq_len = reinterpret_cast<int*>(g->block + o_sl);
+    g->prefix_len = reinterpret_cast<int*>(g->block + o_pl);
+    g->page_table = reinterpret_cast<int*>(g->block + o_pt);
+    g->ws = g->block + o_ws;
+    // all slots empty, inputs zero; done before capture, so plain memset / memcpy are fine here
+    std::vector<int> rs(depth + 1);
+    for (int b = 0; b <= depth; ++b) rs[b] = b * len_bucket;
+    if ((e = hipMemsetAsync(g->block, 0, o_ws, s)) != hipSuccess ||
+        (e = hipMemcpyAsync(g->row_start, rs.data(), rs.size() * 4, hipMemcpyHostToDevice, s)) != hipSuccess ||
+        (e = hipStreamSynchronize(s)) != hipSuccess) {
+        laps_set_error("graph_capture: staging init failed: %s", hipGetErrorString(e));
+        return fail(LAPS_EHIP);
+    }
+    const BatchDesc b{depth, (int)M, g->row_start, g->seq_len, g->prefix_len, g->page_table, max_pages};
+    // warm-up pass: loads code objects and sets kernel attributes outside the capture
+    int rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s);
+    if (rc == LAPS_OK && (e = hipStreamSynchronize(s)) != hipSuccess) {
+        laps_set_error("graph_capture: warm-up failed: %s", hipGetErrorString(e));
+        rc = LAPS_EHIP;
+    }
+    if (rc != LAPS_OK) return fail(rc);
+    if ((e = hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed)) != hipSuccess) {
+        laps_set_error("graph_capture: hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+        return fail(LAPS_EHIP);
+    }
+    rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s);
+    e = hipStreamEndCapture(s, &g->graph);
+    if (rc != LAPS_OK) return fail(rc);
+    if (e != hipSuccess || !g->graph) {
+        laps_set_error("graph_capture: hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        return fail(LAPS_EHIP);
+    }
+    if ((e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0)) != hipSuccess) {
+        laps_set_error("graph_capture: hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        g->exec = nullptr;
+        return fail(LAPS_EHIP);
+    }
+    *out = g;
+    return LAPS_OK;
+}
+
+extern "C" int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* seq_len, const int32_t* prefix_len,
+                                const int32_t* page_table, const float* x_rows, void* stream) {
+    if (!g || n_real < 0 || n_real > g->depth || (n_real > 0 && (!seq_len || !prefix_len || !page_table))) {
+        laps_set_error("graph_stage: bad slot count or NULL pointer");
+        return LAPS_EINVAL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LAPS_TRY(laps_launch_copy_i32(g->seq_len, seq_len, n_real, n_real, 0, g->depth, s));
+    LAPS_TRY(laps_launch_copy_i32(g->prefix_len, prefix_len, n_real, n_real, 0, g->depth, s));
+    LAPS_TRY(laps_launch_copy_i32(g->page_table, page_table, n_real * g->max_pages, 0, 0, g->depth * g->max_pages, s));
+    if (x_rows && n_real > 0)
+        LAPS_HIP(hipMemcpyAsync(g->x_in, x_rows, (size_t)n_real * g->len_bucket * g->ctx->cfg.hidden * 4,
+                                hipMemcpyDeviceToDevice, s));
+    return LAPS_OK;
+}
+
+extern "C" int laps_graph_replay(laps_graph* g, void* stream) {
+    if (!g || !g->exec) {
+        laps_set_error("graph_replay: NULL graph");
+        return LAPS_EINVAL;
+    }
+    LAPS_HIP(hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)));
+    return LAPS_OK;
+}
+
+extern "C" const float* laps_graph_output(const laps_graph* g) { return g ? g->x_out : nullptr; }
+extern "C" float* laps_graph_input(laps_graph* g) { return g ? g->x_in : nullptr; }
+extern "C" int laps_graph_read_output(const laps_graph* g, int32_t n_rows, float* dst, void* stream) {
+    if (!g || !dst || n_rows < 0 || n_rows > g->depth * g->len_bucket) {
+        laps_set_error("graph_read_output: NULL pointer or row count out of range");
+        return LAPS_EINVAL;
+    }
+    if (n_rows == 0) return LAPS_OK;
+    LAPS_HIP(hipMemcpyAsync(dst, g->x_out, (size_t)n_rows * g->ctx->cfg.hidden * 4, hipMemcpyDeviceToDevice,
+                            static_cast<hipStream_t>(stream)));
+    return LAPS_OK;
+}
+extern "C" size_t laps_graph_device_bytes(const laps_graph* g) { return g ? g->block_bytes : 0; }
+
+extern "C" void laps_graph_destroy(laps_graph* g) {
+    if (!g) return;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    if (g->block) (void)hipFree(g->block);
+    delete g;
+}

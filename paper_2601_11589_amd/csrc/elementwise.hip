@@ -1,0 +1,365 @@
+// Row-wise kernels around the GEMMs: token metadata, RMSNorm, split-K reductions fused with the
+// layer's element-wise steps (residual + next RMSNorm, RoPE + KV append, SwiGLU), weight packing
+// and KV cache moves.  All are bandwidth-trivial next to the GEMMs; they use one workgroup per
+// row with 16-byte accesses.
+#include "laps_internal.h"
+
+namespace {
+
+constexpr int ROW_THREADS = 256;
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();  // red may still be read from a previous call
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < ROW_THREADS / 64; ++w) t += red[w];
+    return t;
+}
+
+// ------------------------------------------------------------------ rope table (fp64 evaluation)
+__global__ void rope_table_kernel(float2* table, int max_pos, int half, double theta, int hd) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= max_pos * half) return;
+    const int p = i / half, j = i % half;
+    const double inv_freq = pow(theta, -2.0 * (double)j / (double)hd);
+    const double ang = (double)p * inv_freq;
+    table[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// ------------------------------------------------------------------ token metadata
+// One thread per row: owning sequence by binary search over row_start, then absolute position and
+// KV slot (page * 16 + offset) of the token; -1 for padding rows.
+__global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_start, const int* __restrict__ seq_len,
+                            const int* __restrict__ prefix_len, const int* __restrict__ page_table, int max_pages,
+                            int* __restrict__ new_len_out, int* __restrict__ tok_pos, int* __restrict__ tok_slot) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row < n_seq) {
+        const int cap = row_start[row + 1] - row_start[row];
+        int l = seq_len ? seq_len[row] : cap;
+        l = l < 0 ? 0 : (l > cap ? cap : l);
+        new_len_out[row] = l;
+    }
+    if (row >= n_rows) return;
+    int lo = 0, hi = n_seq;  // find s with row_start[s] <= row < row_start[s+1]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (row_start[mid] <= row) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const int t = row - row_start[s];
+    const int cap = row_start[s + 1] - row_start[s];
+    int l = seq_len ? seq_len[s] : cap;
+    l = l > cap ? cap : l;
+    int pos = -1, slot = -1;
+    if (t >= 0 && t < l) {
+        pos = prefix_len[s] + t;
+        const int page = page_table[(size_t)s * max_pages + pos / LAPS_PAGE];
+        slot = page * LAPS_PAGE + pos % LAPS_PAGE;
+    }
+    tok_pos[row] = pos;
+    tok_slot[row] = slot;
+}
+
+// ------------------------------------------------------------------ RMSNorm: fp32 row -> bf16 row
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x,
+                                                               const bf16_t* __restrict__ w, bf16_t* __restrict__ out,
+                                                               int d, float eps) {
+    __shared__ float red[ROW_THREADS / 64];
+    const size_t row = blockIdx.x;
+    const f32x4* xr = reinterpret_cast<const f32x4*>(x + row * d);
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d / 4; i += ROW_THREADS) {
+        const f32x4 v = xr[i];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    const float inv = rsqrtf(block_sum(ss, red) / (float)d + eps);
+    u32x2* orow = reinterpret_cast<u32x2*>(out + row * d);
+    const u32x2* wr = reinterpret_cast<const u32x2*>(w);
+    for (int i = threadIdx.x; i < d / 4; i += ROW_THREADS) {
+        const f32x4 v = xr[i];
+        const u32x2 g = wr[i];
+        u32x2 o;
+        o.x = pack_bf16x2(v.x * inv * __uint_as_float(g.x << 16), v.y * inv * __uint_as_float(g.x & 0xffff0000u));
+        o.y = pack_bf16x2(v.z * inv * __uint_as_float(g.y << 16), v.w * inv * __uint_as_float(g.y & 0xffff0000u));
+        orow[i] = o;
+    }
+}
+
+// ------------------------------------------------------------------ sum K slices + residual (+ RMSNorm)
+// x_out[row] = resid[row] (or 0 if resid is null) + sum_s partial[s][row]; optionally r_out[row] = rmsnorm(x_out[row]) in bf16.
+// The row is kept in registers between the two passes (d <= 4 * 256 * MAXV).
+template <int MAXV>
+__global__ __launch_bounds__(ROW_THREADS) void epi_resid_kernel(const float* __restrict__ partial, int split,
+                                                                 size_t slice_stride, const float* __restrict__ resid,
+                                                                 float* __restrict__ x_out,
+                                                                 const bf16_t* __restrict__ ln_w,
+                                                                 bf16_t* __restrict__ r_out, int d, float eps) {
+    __shared__ float red[ROW_THREADS / 64];
+    const size_t row = blockIdx.x;
+    const int nv = d / 4;
+    f32x4 v[MAXV];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+        const int i = threadIdx.x + j * ROW_THREADS;
+        if (i < nv) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+            if (resid) a = reinterpret_cast<const f32x4*>(resid + row * d)[i];
+            for (int s = 0; s < split; ++s) a += reinterpret_cast<const f32x4*>(partial + s * slice_stride + row * d)[i];
+            reinterpret_cast<f32x4*>(x_out + row * d)[i] = a;
+            v[j] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
+    }
+    if (ln_w == nullptr) return;
+    const float inv = rsqrtf(block_sum(ss, red) / (float)d + eps);
+    const u32x2* wr = reinterpret_cast<const u32x2*>(ln_w);
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+        const int i = threadIdx.x + j * ROW_THREADS;
+        if (i < nv) {
+            const u32x2 g = wr[i];
+            u32x2 o;
+            o.x = pack_bf16x2(v[j].x * inv * __uint_as_float(g.x << 16), v[j].y * inv * __uint_as_float(g.x & 0xffff0000u));
+            o.y = pack_bf16x2(v[j].z * inv * __uint_as_float(g.y << 16), v[j].w * inv * __uint_as_float(g.y & 0xffff0000u));
+            reinterpret_cast<u32x2*>(r_out + row * d)[i] = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ sum K slices + bias + RoPE + KV append
+// One workgroup per token row.  Work item = one rotate-half pair (j, j + hd/2) of one head; v heads
+// are copied unrotated.  q goes to q_out[row]; k, v go to the token's slot in the paged pools.
+__global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __restrict__ partial, int split,
+                                                               size_t slice_stride, const bf16_t* __restrict__ bias,
+                                                               const int* __restrict__ tok_pos,
+                                                               const int* __restrict__ tok_slot,
+                                                               const float2* __restrict__ rope, int max_pos,
+                                                               bf16_t* __restrict__ q_out,
+                                                               bf16_t* __restrict__ k_pool, bf16_t* __restrict__ v_pool,
+                                                               int n_q, int n_kv, int hd) {
+    const size_t row = blockIdx.x;
+    const int pos = tok_pos[row], slot = tok_slot[row];
+    const int half = hd / 2;
+    const int width = (n_q + 2 * n_kv) * hd;
+    const int n_items = (n_q + 2 * n_kv) * half;
+    const int page = slot >= 0 ? slot / LAPS_PAGE : 0, off = slot >= 0 ? slot % LAPS_PAGE : 0;
+    for (int it = threadIdx.x; it < n_items; it += ROW_THREADS) {
+        const int head = it / half, j = it % half;
+        const int c0 = head * hd + j, c1 = c0 + half;
+        float a = 0.f, b = 0.f;
+        for (int s = 0; s < split; ++s) {
+            const float* p = partial + s * slice_stride + row * width;
+            a += p[c0];
+            b += p[c1];
+        }
+        if (bias) {
+            a += bf16_to_f32(bias[c0]);
+            b += bf16_to_f32(bias[c1]);
+        }
+        if (pos < 0) {  // padding row: defined q (zero), no cache write
+            if (head < n_q) {
+                q_out[row * (size_t)(n_q * hd) + c0] = 0;
+                q_out[row * (size_t)(n_q * hd) + c1] = 0;
+            }
+            continue;
+        }
+        if (head < n_q + n_kv) {
+            // positions past the table are the caller's error; clamp so that the read stays in bounds
+            const float2 cs = rope[(size_t)(pos < max_pos ? pos : max_pos - 1) * half + j];
+            const float ra = a * cs.x - b * cs.y;
+            const float rb = b * cs.x + a * cs.y;
+            a = ra;
+            b = rb;
+        }
+        if (head < n_q) {
+            q_out[row * (size_t)(n_q * hd) + c0] = f32_to_bf16(a);
+            q_out[row * (size_t)(n_q * hd) + c1] = f32_to_bf16(b);
+        } else if (head < n_q + n_kv) {
+            const int g = head - n_q;
+            bf16_t* dst = k_pool + (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd;
+            dst[j] = f32_to_bf16(a);
+            dst[j + half] = f32_to_bf16(b);
+        } else {
+            const int g = head - n_q - n_kv;
+            bf16_t* dst = v_pool + ((size_t)page * n_kv + g) * hd * LAPS_PAGE + off;
+            dst[(size_t)j * LAPS_PAGE] = f32_to_bf16(a);
+            dst[(size_t)(j + half) * LAPS_PAGE] = f32_to_bf16(b);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ sum K slices + SwiGLU
+// Packed gate/up columns: block b of 64 columns = gate cols [32b, 32b+32) then up cols [32b, 32b+32).
+__global__ __launch_bounds__(ROW_THREADS) void epi_swiglu_kernel(const float* __restrict__ partial, int split,
+                                                                  size_t slice_stride, bf16_t* __restrict__ act,
+                                                                  int inter) {
+    const size_t row = blockIdx.x;
+    const int width = 2 * inter;
+    for (int c4 = threadIdx.x; c4 < inter / 4; c4 += ROW_THREADS) {
+        const int c = c4 * 4;
+        const int blk = c / 32, in = c % 32;
+        const size_t gcol = (size_t)blk * 64 + in;
+        f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < split; ++s) {
+            const float* p = partial + s * slice_stride + row * width;
+            g += *reinterpret_cast<const f32x4*>(p + gcol);
+            u += *reinterpret_cast<const f32x4*>(p + gcol + 32);
+        }
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
+        u32x2 w;
+        w.x = pack_bf16x2(o.x, o.y);
+        w.y = pack_bf16x2(o.z, o.w);
+        *reinterpret_cast<u32x2*>(act + row * inter + c) = w;
+    }
+}
+
+// ------------------------------------------------------------------ gate/up interleave
+__global__ void pack_gate_up_kernel(const u32x4* __restrict__ wg, const u32x4* __restrict__ wu, u32x4* __restrict__ dst,
+                                    int inter, int row_vecs) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)2 * inter * row_vecs;
+    if (i >= total) return;
+    const size_t drow = i / row_vecs, v = i % row_vecs;
+    const size_t blk = drow / 64, in = drow % 64;
+    const size_t srow = blk * 32 + (in % 32);
+    dst[i] = (in < 32 ? wg : wu)[srow * row_vecs + v];
+}
+
+// ------------------------------------------------------------------ token-major K/V <-> pools
+template <bool SCATTER>
+__global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ cu, const int* __restrict__ start_pos,
+                               const int* __restrict__ page_table, int max_pages, bf16_t* __restrict__ k_tok,
+                               bf16_t* __restrict__ v_tok, bf16_t* __restrict__ k_pool, bf16_t* __restrict__ v_pool,
+                               int n_kv, int hd) {
+    const int tok = blockIdx.x;
+    if (tok >= n_tokens) return;
+    int lo = 0, hi = n_seq;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= tok) lo = mid; else hi = mid;
+    }
+    const int pos = start_pos[lo] + (tok - cu[lo]);
+    const int page = page_table[(size_t)lo * max_pages + pos / LAPS_PAGE], off = pos % LAPS_PAGE;
+    for (int i = threadIdx.x; i < n_kv * hd; i += blockDim.x) {
+        const int g = i / hd, e = i % hd;
+        const size_t kp = (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd + e;
+        const size_t vp = (((size_t)page * n_kv + g) * hd + e) * LAPS_PAGE + off;
+        const size_t tp = (size_t)tok * n_kv * hd + i;
+        if (SCATTER) {
+            k_pool[kp] = k_tok[tp];
+            v_pool[vp] = v_tok[tp];
+        } else {
+            k_tok[tp] = k_pool[kp];
+            v_tok[tp] = v_pool[vp];
+        }
+    }
+}
+
+// dst[i] = src[i] for i < n; dst[i] = fill_value for fill_from <= i < total (used to stage graph
+// metadata without memset nodes)
+__global__ void copy_fill_i32_kernel(int* __restrict__ dst, const int* __restrict__ src, int n, int fill_value, int total) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    dst[i] = (i < n) ? src[i] : fill_value;
+}
+
+}  // namespace
+
+int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s) {
+    const int half = head_dim / 2;
+    const int n = max_pos * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, table, max_pos, half, (double)theta,
+                       head_dim);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq_len, const int* prefix_len,
+                     const int* page_table, int max_pages, int* new_len_out, int* tok_pos, int* tok_slot,
+                     hipStream_t s) {
+    const int n = n_rows > n_seq ? n_rows : n_seq;
+    hipLaunchKernelGGL(prep_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n_rows, n_seq, row_start, seq_len,
+                       prefix_len, page_table, max_pages, new_len_out, tok_pos, tok_slot);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, hipStream_t s) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, x, w, out, d, eps);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_epi_resid(const float* partial, int split, const float* resid, float* x_out, const bf16_t* ln_w,
+                          bf16_t* r_out, int rows, int d, float eps, hipStream_t s) {
+    const size_t stride = (size_t)rows * d;
+    if (d <= 4 * ROW_THREADS * 2)
+        hipLaunchKernelGGL(epi_resid_kernel<2>, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, resid, x_out,
+                           ln_w, r_out, d, eps);
+    else if (d <= 4 * ROW_THREADS * 8)
+        hipLaunchKernelGGL(epi_resid_kernel<8>, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, resid, x_out,
+                           ln_w, r_out, d, eps);
+    else {
+        laps_set_error("hidden size %d too large for the fused residual + norm kernel", d);
+        return LAPS_EINVAL;
+    }
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_epi_qkv(const float* partial, int split, const bf16_t* bias, const int* tok_pos, const int* tok_slot,
+                        const float2* rope, int max_pos, bf16_t* q_out, bf16_t* k_pool, bf16_t* v_pool, int rows,
+                        int n_q, int n_kv, int hd, hipStream_t s) {
+    const size_t stride = (size_t)rows * (n_q + 2 * n_kv) * hd;
+    hipLaunchKernelGGL(epi_qkv_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, bias, tok_pos,
+                       tok_slot, rope, max_pos, q_out, k_pool, v_pool, n_q, n_kv, hd);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, hipStream_t s) {
+    const size_t stride = (size_t)rows * 2 * inter;
+    hipLaunchKernelGGL(epi_swiglu_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, act, inter);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, int inter, int d, hipStream_t s) {
+    const int row_vecs = d / 8;
+    const size_t total = (size_t)2 * inter * row_vecs;
+    hipLaunchKernelGGL(pack_gate_up_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const u32x4*>(wg), reinterpret_cast<const u32x4*>(wu),
+                       reinterpret_cast<u32x4*>(dst), inter, row_vecs);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
+                        const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
+                        bf16_t* v_pool, int n_kv, int hd, hipStream_t s) {
+    if (n_tokens == 0) return LAPS_OK;
+    if (scatter)
+        hipLaunchKernelGGL(kv_move_kernel<true>, dim3(n_tokens), dim3(256), 0, s, n_seq, n_tokens, cu, start_pos,
+                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd);
+    else
+        hipLaunchKernelGGL(kv_move_kernel<false>, dim3(n_tokens), dim3(256), 0, s, n_seq, n_tokens, cu, start_pos,
+                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s) {
+    (void)fill_from;
+    if (total <= 0) return LAPS_OK;
+    hipLaunchKernelGGL(copy_fill_i32_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dst, src, n, fill_value, total);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}

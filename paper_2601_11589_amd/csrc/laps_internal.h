@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of liblaps (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/laps.h"
+
+typedef unsigned short bf16_t;  // storage: upper half of a float32
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+static __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((unsigned)b) << 16); }
+static __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    __bf16 h = (__bf16)f;  // v_cvt_pk_bf16_f32: round-to-nearest-even
+    return __builtin_bit_cast(bf16_t, h);
+}
+static __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+
+void laps_set_error(const char* fmt, ...);
+#define LAPS_HIP(call)                                                                         \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            laps_set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return LAPS_EHIP;                                                                  \
+        }                                                                                      \
+    } while (0)
+#define LAPS_LAUNCH_CHECK()                                                                    \
+    do {                                                                                       \
+        hipError_t e_ = hipGetLastError();                                                     \
+        if (e_ != hipSuccess) {                                                                \
+            laps_set_error("kernel launch failed: %s (%s:%d)", hipGetErrorString(e_), __FILE__, __LINE__); \
+            return LAPS_EHIP;                                                                  \
+        }                                                                                      \
+    } while (0)
+
+// ----------------------------------------------------------------------------- GEMM
+// C = A[M,K] * W[N,K]^T, bf16 operands, fp32 accumulation, K-split into `split` slices.
+enum GemmEpi {
+    EPI_PARTIAL = 0,  // out_f32[split][M][N] raw partial sums
+};
+struct GemmPlan {
+    int cfg;        // 0: 128x128 tile (skinny / bandwidth-bound), 1: 256x256 tile
+    int split;      // K slices
+    int k_per_split;  // multiple of 64
+};
+GemmPlan laps_gemm_plan(int m, int n, int k, int force_split);
+size_t laps_gemm_partial_bytes(int m, int n, int k);
+int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, float* partial, int m, int n, int k,
+                     hipStream_t s);
+
+// ----------------------------------------------------------------------------- element-wise / epilogues
+int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s);
+int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq_len, const int* prefix_len,
+                     const int* page_table, int max_pages, int* new_len_out, int* tok_pos, int* tok_slot,
+                     hipStream_t s);
+int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, hipStream_t s);
+// x_out = resid + sum_s partial[s]; if ln_w: r_out = rmsnorm(x_out; ln_w) in bf16.
+int laps_launch_epi_resid(const float* partial, int split, const float* resid, float* x_out, const bf16_t* ln_w,
+                          bf16_t* r_out, int rows, int d, float eps, hipStream_t s);
+int laps_launch_epi_qkv(const float* partial, int split, const bf16_t* bias, const int* tok_pos, const int* tok_slot,
+                        const float2* rope, int max_pos, bf16_t* q_out, bf16_t* k_pool, bf16_t* v_pool, int rows,
+                        int n_q, int n_kv, int hd, hipStream_t s);
+int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, hipStream_t s);
+int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, int inter, int d, hipStream_t s);
+int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
+                        const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
+                        bf16_t* v_pool, int n_kv, int hd, hipStream_t s);
+int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s);
+
+// ----------------------------------------------------------------------------- attention
+int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
+                          const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
+                          int max_pages, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv, int hd,
+                          hipStream_t s);
