@@ -1,0 +1,339 @@
+#!/usr/bin/env python3
+"""Benchmark of the ragged-prefill hot path on one MI355X.
+
+Primary workload (benchmark configs[1]): 256 new prompts, lengths U[8,64], bucketed to
+{16,32,64}, 4-layer stack of 32B-shaped layers, every bucket batch replayed as a captured
+hipGraph.  One "step" = plan + stage + replay of every batch of the 256 requests.
+Also reported in the same JSON line: the long-prefill workload (configs[3]) as `long_prefill`,
+the token-max variant of the short workload as `short_token_max`, and the fp64 oracle timed on
+the host cores as `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "prefill tokens/s + p90 latency; % MFMA peak (long) / % HBM peak (short) at 1 GPU"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFS = 2500.0
+LEN_BUCKETS = [16, 32, 64]
+DEPTHS = [1, 2, 4, 8, 16, 32, 64]
+LONG_CHUNK = 2048
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def pct(v, q):
+    import numpy as np
+    return float(np.percentile(np.asarray(v, dtype=np.float64), q)) if len(v) else None
+
+
+def gemm_shapes(cfg):
+    qd = cfg.n_q_heads * cfg.head_dim
+    return {"gemm_qkv": (cfg.qkv_dim, cfg.hidden), "gemm_o": (cfg.hidden, qd),
+            "gemm_gateup": (2 * cfg.intermediate, cfg.hidden), "gemm_down": (cfg.hidden, cfg.intermediate)}
+
+
+def attn_flops(cfg, new_len, prefix_len):
+    """Causal-triangle flops only: 4 * hd * n_q * (L*H + L(L+1)/2) per sequence per layer."""
+    tot = 0
+    for l, h in zip(new_len, prefix_len):
+        l, h = int(l), int(h)
+        tot += 4 * cfg.head_dim * cfg.n_q_heads * (l * h + l * (l + 1) // 2)
+    return tot
+
+
+def build_model(cfg, seed):
+    from paper_2601_11589_amd import api, inputs
+    ctx = api.LapsCtx(cfg, max_positions=8192 + 64)
+    layers = []
+    host_layers = []
+    t0 = time.perf_counter()
+    for l in range(cfg.n_layers):
+        w = inputs.make_layer_weights(cfg, seed, l, threads=min(16, os.cpu_count() or 8))
+        layers.append(ctx.upload_layer(w))
+        host_layers.append(w)
+        log(f"[bench] layer {l} weights generated + uploaded ({time.perf_counter() - t0:.1f}s)")
+    return ctx, layers, host_layers
+
+
+# ------------------------------------------------------------------------------------- short buckets
+def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, tag):
+    import numpy as np
+    import torch
+    from paper_2601_11589_amd import api, inputs, runner
+
+    seed = inputs.SEED_BASE + 2
+    b = inputs.make_batch(2)
+    T = b.n_tokens
+    d_x = torch.from_numpy(inputs.make_activations(cfg, seed, T)).cuda()
+    k_pools, v_pools = ctx.new_pools(b.n_pages, cfg.n_layers)
+    plan_args = (64, LEN_BUCKETS, DEPTHS, token_budget, LONG_CHUNK, b.new_len, b.prefix_len)
+    plan = api.laps_plan_buckets(*plan_args)
+    assert not plan["longs"]
+    staged = runner.stage_short_batches(plan, b.new_len, b.prefix_len, b.page_table, b.cu_seqlens, d_x, cfg.hidden)
+    max_rows = max(s.depth * s.len_bucket for s in staged)
+    ctx.workspace(max_rows, max(s.depth for s in staged))
+    stream = torch.cuda.Stream()
+    sr = runner.ShortRunner(ctx, layers, k_pools, v_pools, b.page_table.shape[1], stream)
+    for s in staged:                      # capture every needed shape
+        sr.graph_for(s.len_bucket, s.depth)
+    shapes = sorted(sr.graphs.keys())
+    log(f"[bench:{tag}] {len(staged)} batches, shapes {shapes}, capture s/graph "
+        f"{[round(sr.capture_s[k], 3) for k in shapes]}, graph MB "
+        f"{[round(sr.graphs[k].laps_graph_device_bytes() / 1e6, 1) for k in shapes]}")
+    for _ in range(warmup):
+        for s in staged:
+            sr.run(s)
+    stream.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in staged]
+          for _ in range(steps)]
+    plan_us = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        tp = time.perf_counter()
+        api.laps_plan_buckets(*plan_args)            # the integer plan is part of every step
+        plan_us.append((time.perf_counter() - tp) * 1e6)
+        for j, s in enumerate(staged):
+            ev[k][j][0].record(stream)
+            sr.run(s)
+            ev[k][j][1].record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    lat = []                                          # per request: duration of the batch that served it
+    for k in range(steps):
+        for j, s in enumerate(staged):
+            ms = ev[k][j][0].elapsed_time(ev[k][j][1])
+            lat += [ms] * s.n_real
+    res = {"tokens_per_s": T * steps / wall, "ms_per_step": wall / steps * 1e3, "real_tokens": T,
+           "padded_rows": int(sum(s.depth * s.len_bucket for s in staged)), "n_batches": len(staged),
+           "token_budget": token_budget, "latency_ms_p50": pct(lat, 50), "latency_ms_p90": pct(lat, 90),
+           "plan_us": float(np.median(plan_us)), "graph_shapes": [list(k) for k in shapes],
+           "graph_capture_s": {f"{k[0]}x{k[1]}": round(sr.capture_s[k], 4) for k in shapes},
+           "graph_device_MB": {f"{k[0]}x{k[1]}": round(sr.graphs[k].laps_graph_device_bytes() / 1e6, 2) for k in shapes}}
+    if profile_kernels:
+        # same kernels, same shapes, un-captured, every launch bracketed by HIP events on its stream
+        ctx.laps_prof_enable(True)
+        padded = []
+        for s in staged:
+            M = s.depth * s.len_bucket
+            x = torch.zeros((M, cfg.hidden), dtype=torch.float32, device="cuda")
+            x[: s.x_rows.shape[0]] = s.x_rows
+            sl = torch.zeros(s.depth, dtype=torch.int32, device="cuda")
+            sl[: s.n_real] = s.seq_len
+            pl = torch.zeros(s.depth, dtype=torch.int32, device="cuda")
+            pl[: s.n_real] = s.prefix_len
+            pt = torch.zeros((s.depth, s.page_table.shape[1]), dtype=torch.int32, device="cuda")
+            pt[: s.n_real] = s.page_table
+            cu = torch.arange(0, (s.depth + 1) * s.len_bucket, s.len_bucket, dtype=torch.int32, device="cuda")
+            padded.append((cu, sl, pl, pt, x, M))
+        torch.cuda.synchronize()
+        gbytes = 0.0
+        gflops = 0.0
+        with torch.cuda.stream(stream):
+            for (cu, sl, pl, pt, x, M) in padded:
+                ctx.laps_prefill_stack(layers, cu, sl, pl, pt, k_pools, v_pools, x, None, stream)
+                for (n, kk) in gemm_shapes(cfg).values():
+                    gbytes += cfg.n_layers * (n * kk * 2 + M * kk * 2 + M * n * 4)
+                    gflops += cfg.n_layers * 2.0 * M * n * kk
+        stream.synchronize()
+        prof = ctx.laps_prof_read()
+        ctx.laps_prof_enable(False)
+        gms = sum(prof[k][0] for k in gemm_shapes(cfg))
+        gcnt = sum(prof[k][1] for k in gemm_shapes(cfg))
+        res["kernel_ms"] = {k: round(v[0], 4) for k, v in prof.items()}
+        res["kernel_launches"] = {k: v[1] for k, v in prof.items()}
+        res["gemm"] = {"launches": gcnt, "avg_us": gms / gcnt * 1e3, "bytes_per_launch": gbytes / gcnt,
+                       "GBps": gbytes / (gms * 1e-3) / 1e9, "TFLOPs": gflops / (gms * 1e-3) / 1e12}
+    sr.close()
+    return res
+
+
+# ------------------------------------------------------------------------------------- long prefill
+def run_long(ctx, layers, cfg, steps, warmup):
+    import numpy as np
+    import torch
+    from paper_2601_11589_amd import api, inputs, runner
+
+    seed = inputs.SEED_BASE + 4
+    b = inputs.make_batch(4)
+    T = b.n_tokens
+    d_x = torch.from_numpy(inputs.make_activations(cfg, seed, T)).cuda()
+    out = torch.empty_like(d_x)
+    k_pools, v_pools = ctx.new_pools(b.n_pages, cfg.n_layers)
+    plan = api.laps_plan_buckets(64, LEN_BUCKETS, DEPTHS, 128, LONG_CHUNK, b.new_len, b.prefix_len)
+    assert len(plan["longs"]) == b.n and not plan["batches"]
+    ctx.workspace(LONG_CHUNK, 1)
+    stream = torch.cuda.Stream()
+    cu = b.cu_seqlens
+    d_pt = torch.from_numpy(b.page_table).cuda()
+    jobs = []
+    for lg in plan["longs"]:
+        i, done = lg["req_id"], 0
+        for c in lg["chunks"]:
+            jobs.append((i, done, c, torch.tensor([0, c], dtype=torch.int32, device="cuda"),
+                         torch.tensor([done], dtype=torch.int32, device="cuda")))
+            done += c
+
+    def one_pass(events=None):
+        for j, (i, done, c, d_cu, d_pre) in enumerate(jobs):
+            lo = int(cu[i]) + done
+            if events is not None and done == 0:
+                events[i][0].record(stream)
+            ctx.laps_prefill_stack(layers, d_cu, None, d_pre, d_pt[i:i + 1], k_pools, v_pools, d_x[lo:lo + c],
+                                   out[lo:lo + c], stream)
+            if events is not None and done + c == int(b.new_len[i]):
+                events[i][1].record(stream)
+
+    for _ in range(warmup):
+        one_pass()
+    stream.synchronize()
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(b.n)]
+           for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        one_pass(evs[k])
+    stream.synchronize()
+    wall = time.perf_counter() - t0
+    lat = [evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(steps) for i in range(b.n)]
+    # algorithmic flops: GEMMs on real tokens + causal attention triangle
+    gemm_fl = 2.0 * cfg.params_per_layer * T * cfg.n_layers
+    att_fl = float(attn_flops(cfg, b.new_len, b.prefix_len)) * cfg.n_layers
+    res = {"tokens_per_s": T * steps / wall, "ms_per_step": wall / steps * 1e3, "real_tokens": T,
+           "chunk": LONG_CHUNK, "n_chunks": len(jobs), "latency_ms_p50": pct(lat, 50), "latency_ms_p90": pct(lat, 90),
+           "algorithmic_TFLOP_per_step": (gemm_fl + att_fl) / 1e12,
+           "stack_TFLOPs": (gemm_fl + att_fl) * steps / wall / 1e12,
+           "stack_frac_of_mfma_peak": (gemm_fl + att_fl) * steps / wall / 1e12 / MFMA_BF16_PEAK_TFS}
+    # per-kernel pass
+    ctx.laps_prof_enable(True)
+    one_pass()
+    stream.synchronize()
+    prof = ctx.laps_prof_read()
+    ctx.laps_prof_enable(False)
+    res["kernel_ms"] = {k: round(v[0], 3) for k, v in prof.items()}
+    res["kernel_launches"] = {k: v[1] for k, v in prof.items()}
+    n, kk = gemm_shapes(cfg)["gemm_gateup"]
+    ms, cnt = prof["gemm_gateup"]
+    fl = 2.0 * T * n * kk * cfg.n_layers          # all chunks of all prompts, real rows only
+    res["roofline"] = {"bound": "mfma", "kernel": "gemm (gate/up projection, 256x256 tile)", "achieved": fl / (ms * 1e-3) / 1e12,
+                       "peak": MFMA_BF16_PEAK_TFS, "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFS,
+                       "traffic": None, "avg_launch_us": ms / cnt * 1e3, "launches": cnt}
+    ms_all = sum(prof[k][0] for k in gemm_shapes(cfg))
+    res["all_gemm_TFLOPs"] = gemm_fl / (ms_all * 1e-3) / 1e12
+    ams, acnt = prof["attn"]
+    res["attention_TFLOPs"] = att_fl / (ams * 1e-3) / 1e12 if ams > 0 else None
+    return res
+
+
+# ------------------------------------------------------------------------------------- oracle on host cores
+def cpu_baseline(cfg, host_layers, n_sample_req=24, n_layers=None):
+    """fp64 oracle, as it stands, on the first requests of the short workload; all host cores BLAS uses."""
+    import numpy as np
+    from oracle import laps_oracle as O
+    from paper_2601_11589_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n_layers = n_layers or cfg.n_layers
+    b = inputs.make_batch(2)
+    lens = [int(v) for v in b.new_len[:n_sample_req]]
+    T = sum(lens)
+    x = inputs.make_activations(cfg, inputs.SEED_BASE + 2, b.n_tokens)[:T].astype(np.float64)
+
+    class Lazy:
+        def __len__(self):
+            return n_layers
+
+        def __getitem__(self, i):
+            return {k: inputs.bf16_bits_to_f64(v) for k, v in host_layers[i].items()}
+
+    t0 = time.perf_counter()
+    O.stack_forward(cfg, Lazy(), x, lens)
+    dt = time.perf_counter() - t0
+    return {"value": T / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n_sample_req} requests ({T} tokens) of the short-bucket workload through all "
+                      f"{n_layers} layers, numpy float64 (weights widened from bf16 inside the timed region), {dt:.1f}s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--token-budget", type=int, default=128, help="padded tokens per captured short graph")
+    ap.add_argument("--no-long", action="store_true", help="skip the long-prefill workload")
+    ap.add_argument("--no-token-max", action="store_true", help="skip the token-max variant of the short workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--long-steps", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (replicas are independent; see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_11589_amd import api, inputs
+    api.lib()                                           # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    props = torch.cuda.get_device_properties(0)
+    log(f"[bench] device {props.name}, {props.multi_processor_count} CUs, {props.total_memory / 2**30:.0f} GiB; "
+        f"peaks used: HBM {HBM_PEAK_GBS} GB/s, bf16 MFMA {MFMA_BF16_PEAK_TFS} TFLOP/s")
+    cfg = inputs.qwen32b_cfg(4)
+    ctx, layers, host_layers = build_model(cfg, inputs.SEED_BASE + 2)
+
+    short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short")
+    g = short.pop("gemm")
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("short_gemm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    line = {
+        "metric": METRIC, "value": short["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": short["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: 256 new prompts U[8,64], buckets {16,32,64}, 4-layer Qwen2.5-32B-shaped stack, "
+                               f"hipGraph per (bucket, depth), token_budget {args.token_budget} padded tokens per graph",
+                   "layers": cfg.n_layers, "requests": 256, "token_budget": args.token_budget},
+        "latency_ms": {"p50": short["latency_ms_p50"], "p90": short["latency_ms_p90"],
+                       "what": "per request: stage+replay time of the bucket batch that serves it"},
+        "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<128,128,2,2> (all four projections)",
+                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g["GBps"] / HBM_PEAK_GBS,
+                     "traffic": traffic, "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"],
+                     "launches": g["launches"], "TFLOPs": g["TFLOPs"]},
+        "short": short,
+    }
+    if not args.no_token_max:
+        tm = run_short(ctx, layers, cfg, 4096, max(2, args.steps // 2), 1, True, "token-max")
+        gm = tm.pop("gemm")
+        tm["gemm_TFLOPs"] = gm["TFLOPs"]
+        tm["gemm_frac_of_mfma_peak"] = gm["TFLOPs"] / MFMA_BF16_PEAK_TFS
+        line["short_token_max"] = tm
+    if not args.no_long:
+        line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(cfg, host_layers)
+    else:
+        line["cpu_baseline"] = None
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

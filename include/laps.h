@@ -21,7 +21,9 @@
  *     laps_ctx, laps_plan, laps_graph and what those allocate internally.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  laps_prefill_*,
  *     laps_graph_stage and laps_graph_replay only enqueue work: they never synchronise the
- *     stream and never allocate device memory.
+ *     stream and never allocate device memory.  The kernels they enqueue read the device arrays
+ *     passed in (lengths, page tables, inputs, weights, pools) when they run, not when the call
+ *     returns: keep those arrays valid and unchanged until that stream work has completed.
  *   - bf16 = upper 16 bits of an IEEE float32, round-to-nearest-even on conversion.
  *   - Layer math (all accumulation fp32): r = rmsnorm(x; ln1); [q,k,v] = r W_qkv^T (+b);
  *     rotate-half RoPE with theta on q,k at absolute position prefix_len+t; causal grouped-

@@ -137,7 +137,8 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
             const int pi = c / CPP, within = c % CPP;
             int pidx = j0 / LAPS_PAGE + pi;
             pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
-            const size_t page = (size_t)pt[pidx];
+            const int pg = pt[pidx];
+            const size_t page = (size_t)(pg > 0 ? pg : 0);  // an unset (-1) entry must not turn into a wild address
             const size_t off = ((page * n_kv + kvh) * CPP + within);
             kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
             vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];

@@ -59,7 +59,7 @@ __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_s
     if (t >= 0 && t < l) {
         pos = prefix_len[s] + t;
         const int page = page_table[(size_t)s * max_pages + pos / LAPS_PAGE];
-        slot = page * LAPS_PAGE + pos % LAPS_PAGE;
+        slot = page >= 0 ? page * LAPS_PAGE + pos % LAPS_PAGE : -1;  // unset table entry: treat as padding
     }
     tok_pos[row] = pos;
     tok_slot[row] = slot;
@@ -248,6 +248,7 @@ __global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ 
     }
     const int pos = start_pos[lo] + (tok - cu[lo]);
     const int page = page_table[(size_t)lo * max_pages + pos / LAPS_PAGE], off = pos % LAPS_PAGE;
+    if (page < 0) return;  // unset table entry
     for (int i = threadIdx.x; i < n_kv * hd; i += blockDim.x) {
         const int g = i / hd, e = i % hd;
         const size_t kp = (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd + e;
