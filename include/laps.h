@@ -204,7 +204,7 @@ void laps_graph_destroy(laps_graph* g);
 
 /* ------------------------------------------------------------------ single kernels (tests, roofline)
  * C[M,N] (fp32, row-major) = A[M,K] (bf16 row-major) * W[N,K]^T (bf16 row-major).  K % 64 == 0,
- * N % 128 == 0.  `split_k` 0 = automatic choice of the number of K slices.  workspace_dev must hold
+ * N % 64 == 0.  `split_k` 0 = automatic choice of the number of K slices.  workspace_dev must hold
  * laps_gemm_workspace_bytes(m, n, k, split_k) bytes (0 when a single slice is used; then it may be NULL). */
 size_t laps_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t split_k);
 int laps_gemm_bf16(laps_ctx* ctx, const void* a_dev, const void* w_dev, float* c_dev, int32_t m, int32_t n,

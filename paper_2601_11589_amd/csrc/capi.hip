@@ -202,19 +202,23 @@ struct BatchDesc {
     int max_pages;
 };
 
-static int run_gemm(laps_ctx* c, int cls, bool capturing, const bf16_t* a, const bf16_t* w, float* partial, int m, int n,
-                    int k, int* split_out, hipStream_t s) {
-    const GemmPlan p = laps_gemm_plan(m, n, k, 0);
-    *split_out = p.split;
-    ProfScope ps(c, s, cls, capturing);
-    return laps_gemm_launch(p, a, w, partial, m, n, k, s);
-}
-
 #define LAPS_TRY(x)                 \
     do {                            \
         int rc_ = (x);              \
         if (rc_ != LAPS_OK) return rc_; \
     } while (0)
+
+// One projection.  `want` is the epilogue the caller would like fused; the plan falls back to raw
+// K-slice partial sums when it splits K.  Returns the plan so the caller knows which case ran.
+static int run_gemm(laps_ctx* c, int cls, bool capturing, const bf16_t* a, const bf16_t* w, int m, int n, int k,
+                    int want, float* partial, float* out_f32, const float* resid, bf16_t* out_bf16, GemmPlan* plan,
+                    hipStream_t s) {
+    const GemmPlan p = laps_gemm_plan(m, n, k, 0, want);
+    *plan = p;
+    ProfScope ps(c, s, cls, capturing);
+    if (p.epi == EPI_PARTIAL) return laps_gemm_launch(p, a, w, m, n, k, partial, nullptr, nullptr, s);
+    return laps_gemm_launch(p, a, w, m, n, k, out_f32, resid, out_bf16, s);
+}
 
 // Runs layers [0, n_layers) of `w`.  Token metadata (prep) is computed once.
 static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, const BatchDesc& b, void* const* k_pools,
@@ -249,11 +253,13 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         const float* resid = (l == 0) ? x_in : x_out;
         bf16_t* kp = static_cast<bf16_t*>(k_pools[l]);
         bf16_t* vp = static_cast<bf16_t*>(v_pools[l]);
-        int split = 1;
-        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r, static_cast<const bf16_t*>(lw.w_qkv), partial, M, qkv, d, &split, s));
+        GemmPlan gp;
+        // q, k, v: GEMM -> K-slice sums -> bias + RoPE + KV append
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r, static_cast<const bf16_t*>(lw.w_qkv), M, qkv, d, EPI_PARTIAL,
+                          partial, nullptr, nullptr, nullptr, &gp, s));
         {
             ProfScope ps(c, s, LAPS_K_EPI_QKV, capturing);
-            LAPS_TRY(laps_launch_epi_qkv(partial, split, cf.has_qkv_bias ? static_cast<const bf16_t*>(lw.b_qkv) : nullptr,
+            LAPS_TRY(laps_launch_epi_qkv(partial, gp.split, cf.has_qkv_bias ? static_cast<const bf16_t*>(lw.b_qkv) : nullptr,
                                          tok_pos, tok_slot, c->rope, c->max_pos, q, kp, vp, M, cf.n_q_heads,
                                          cf.n_kv_heads, hd, s));
         }
@@ -262,22 +268,36 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
             LAPS_TRY(laps_launch_attention(q, attn, kp, vp, b.row_start, new_len, b.prefix_len, b.page_table, b.max_pages,
                                            b.n_seq, M, tile_start, cf.n_q_heads, cf.n_kv_heads, hd, s));
         }
-        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), partial, M, d, qd, &split, s));
-        {
+        // x_mid = resid + attn W_o^T ; r = rmsnorm(x_mid; ln2)
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), M, d, qd, EPI_RESID,
+                          partial, x_mid, resid, nullptr, &gp, s));
+        if (gp.epi == EPI_RESID) {
+            ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
+            LAPS_TRY(laps_launch_rmsnorm(x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d, cf.rms_eps, s));
+        } else {
             ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
-            LAPS_TRY(laps_launch_epi_resid(partial, split, resid, x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d,
+            LAPS_TRY(laps_launch_epi_resid(partial, gp.split, resid, x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d,
                                            cf.rms_eps, s));
         }
-        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_GATEUP, capturing, r, static_cast<const bf16_t*>(lw.w_gate_up), partial, M, 2 * I, d, &split, s));
-        {
+        // act = silu(r W_g^T) * (r W_u^T)
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_GATEUP, capturing, r, static_cast<const bf16_t*>(lw.w_gate_up), M, 2 * I, d,
+                          EPI_SWIGLU, partial, nullptr, nullptr, act, &gp, s));
+        if (gp.epi != EPI_SWIGLU) {
             ProfScope ps(c, s, LAPS_K_EPI_SWIGLU, capturing);
-            LAPS_TRY(laps_launch_epi_swiglu(partial, split, act, M, I, s));
+            LAPS_TRY(laps_launch_epi_swiglu(partial, gp.split, act, M, I, s));
         }
-        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_DOWN, capturing, act, static_cast<const bf16_t*>(lw.w_down), partial, M, d, I, &split, s));
-        {
+        // x_out = x_mid + act W_d^T ; r = rmsnorm(x_out; next layer's ln1)
+        const bf16_t* next_ln = (l + 1 < n_layers) ? static_cast<const bf16_t*>(w[l + 1].ln1_w) : nullptr;
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_DOWN, capturing, act, static_cast<const bf16_t*>(lw.w_down), M, d, I, EPI_RESID,
+                          partial, x_out, x_mid, nullptr, &gp, s));
+        if (gp.epi == EPI_RESID) {
+            if (next_ln) {
+                ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
+                LAPS_TRY(laps_launch_rmsnorm(x_out, next_ln, r, M, d, cf.rms_eps, s));
+            }
+        } else {
             ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
-            const bf16_t* next_ln = (l + 1 < n_layers) ? static_cast<const bf16_t*>(w[l + 1].ln1_w) : nullptr;
-            LAPS_TRY(laps_launch_epi_resid(partial, split, x_mid, x_out, next_ln, r, M, d, cf.rms_eps, s));
+            LAPS_TRY(laps_launch_epi_resid(partial, gp.split, x_mid, x_out, next_ln, r, M, d, cf.rms_eps, s));
         }
     }
     return LAPS_OK;
@@ -391,8 +411,8 @@ extern "C" int laps_kv_gather(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
 }
 
 extern "C" size_t laps_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t split_k) {
-    if (m < 1 || n < 128 || n % 128 || k < 64 || k % 64 || split_k < 0) return 0;
-    const GemmPlan p = laps_gemm_plan(m, n, k, split_k);
+    if (m < 1 || n < 64 || n % 64 || k < 64 || k % 64 || split_k < 0) return 0;
+    const GemmPlan p = laps_gemm_plan(m, n, k, split_k, EPI_PARTIAL);
     return p.split == 1 ? 0 : (size_t)p.split * m * n * sizeof(float);
 }
 
@@ -402,19 +422,21 @@ extern "C" int laps_gemm_bf16(laps_ctx* c, const void* a, const void* w, float* 
         laps_set_error("gemm: NULL pointer or bad size");
         return LAPS_EINVAL;
     }
-    if (n < 128 || n % 128 || k < 64 || k % 64) {
-        laps_set_error("gemm: need n %% 128 == 0 and k %% 64 == 0 (n=%d k=%d)", n, k);
+    if (n < 64 || n % 64 || k < 64 || k % 64) {
+        laps_set_error("gemm: need n %% 64 == 0 and k %% 64 == 0 (n=%d k=%d)", n, k);
         return LAPS_EINVAL;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const GemmPlan p = laps_gemm_plan(m, n, k, split_k);
-    if (p.split == 1) return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), out, m, n, k, s);
+    const GemmPlan p = laps_gemm_plan(m, n, k, split_k, EPI_PARTIAL);
+    if (p.split == 1)
+        return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, out, nullptr, nullptr, s);
     const size_t need = (size_t)p.split * m * n * sizeof(float);
     if (!ws || ws_bytes < need || ((uintptr_t)ws & 255)) {
         laps_set_error("gemm: split-K needs %zu bytes of 256-byte aligned workspace", need);
         return LAPS_ENOMEM;
     }
-    LAPS_TRY(laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), static_cast<float*>(ws), m, n, k, s));
+    LAPS_TRY(laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, static_cast<float*>(ws),
+                              nullptr, nullptr, s));
     // sum the slices: view [m, n] as rows of `cols` columns, cols | n and cols <= 8192
     int cols = n;
     while (cols > 8192) {

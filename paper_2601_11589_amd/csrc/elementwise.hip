@@ -91,37 +91,63 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __res
 }
 
 // ------------------------------------------------------------------ sum K slices + residual (+ RMSNorm)
-// x_out[row] = resid[row] (or 0 if resid is null) + sum_s partial[s][row]; optionally r_out[row] = rmsnorm(x_out[row]) in bf16.
-// The row is kept in registers between the two passes (d <= 4 * 256 * MAXV).
+// x_out[row] = resid[row] (or 0 if resid is null) + sum_s partial[s][row]; optionally
+// r_out[row] = rmsnorm(x_out[row]) in bf16.  One workgroup of 512 threads per row; the row stays in
+// registers between the two passes (d <= 4 * 512 * MAXV).
+constexpr int RESID_THREADS = 512;
+
+__device__ __forceinline__ float block_sum512(float v, float* red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < RESID_THREADS / 64; ++w) t += red[w];
+    return t;
+}
+
 template <int MAXV>
-__global__ __launch_bounds__(ROW_THREADS) void epi_resid_kernel(const float* __restrict__ partial, int split,
-                                                                 size_t slice_stride, const float* __restrict__ resid,
-                                                                 float* __restrict__ x_out,
-                                                                 const bf16_t* __restrict__ ln_w,
-                                                                 bf16_t* __restrict__ r_out, int d, float eps) {
-    __shared__ float red[ROW_THREADS / 64];
+__global__ __launch_bounds__(RESID_THREADS) void epi_resid_kernel(const float* __restrict__ partial, int split,
+                                                                   size_t slice_stride, const float* __restrict__ resid,
+                                                                   float* __restrict__ x_out,
+                                                                   const bf16_t* __restrict__ ln_w,
+                                                                   bf16_t* __restrict__ r_out, int d, float eps) {
+    __shared__ float red[RESID_THREADS / 64];
     const size_t row = blockIdx.x;
     const int nv = d / 4;
     f32x4 v[MAXV];
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
-        const int i = threadIdx.x + j * ROW_THREADS;
+        const int i = threadIdx.x + j * RESID_THREADS;
         if (i < nv) {
             f32x4 a = {0.f, 0.f, 0.f, 0.f};
             if (resid) a = reinterpret_cast<const f32x4*>(resid + row * d)[i];
-            for (int s = 0; s < split; ++s) a += reinterpret_cast<const f32x4*>(partial + s * slice_stride + row * d)[i];
+            const f32x4* p = reinterpret_cast<const f32x4*>(partial + row * d) + i;
+            const size_t st = slice_stride / 4;
+            int s = 0;
+            for (; s + 4 <= split; s += 4) {  // four independent loads in flight, summed in slice order
+                const f32x4 p0 = p[(size_t)s * st], p1 = p[(size_t)(s + 1) * st], p2 = p[(size_t)(s + 2) * st],
+                            p3 = p[(size_t)(s + 3) * st];
+                a += p0;
+                a += p1;
+                a += p2;
+                a += p3;
+            }
+            for (; s < split; ++s) a += p[(size_t)s * st];
             reinterpret_cast<f32x4*>(x_out + row * d)[i] = a;
             v[j] = a;
             ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
         }
     }
     if (ln_w == nullptr) return;
-    const float inv = rsqrtf(block_sum(ss, red) / (float)d + eps);
+    const float inv = rsqrtf(block_sum512(ss, red) / (float)d + eps);
     const u32x2* wr = reinterpret_cast<const u32x2*>(ln_w);
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
-        const int i = threadIdx.x + j * ROW_THREADS;
+        const int i = threadIdx.x + j * RESID_THREADS;
         if (i < nv) {
             const u32x2 g = wr[i];
             u32x2 o;
@@ -133,8 +159,9 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_resid_kernel(const float* __r
 }
 
 // ------------------------------------------------------------------ sum K slices + bias + RoPE + KV append
-// One workgroup per token row.  Work item = one rotate-half pair (j, j + hd/2) of one head; v heads
-// are copied unrotated.  q goes to q_out[row]; k, v go to the token's slot in the paged pools.
+// Grid (token row, chunk of work items).  Work item = four consecutive rotate-half pairs
+// (j..j+3, j+hd/2..j+hd/2+3) of one head: two 16-byte loads per K slice.  v heads are copied
+// unrotated.  q goes to q_out[row]; k, v go to the token's slot in the paged pools.
 __global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __restrict__ partial, int split,
                                                                size_t slice_stride, const bf16_t* __restrict__ bias,
                                                                const int* __restrict__ tok_pos,
@@ -144,52 +171,68 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __res
                                                                bf16_t* __restrict__ k_pool, bf16_t* __restrict__ v_pool,
                                                                int n_q, int n_kv, int hd) {
     const size_t row = blockIdx.x;
+    const int half = hd / 2, per_head = half / 4;
+    const int n_items = (n_q + 2 * n_kv) * per_head;
+    const int it = blockIdx.y * ROW_THREADS + threadIdx.x;
+    if (it >= n_items) return;
     const int pos = tok_pos[row], slot = tok_slot[row];
-    const int half = hd / 2;
     const int width = (n_q + 2 * n_kv) * hd;
-    const int n_items = (n_q + 2 * n_kv) * half;
-    const int page = slot >= 0 ? slot / LAPS_PAGE : 0, off = slot >= 0 ? slot % LAPS_PAGE : 0;
-    for (int it = threadIdx.x; it < n_items; it += ROW_THREADS) {
-        const int head = it / half, j = it % half;
-        const int c0 = head * hd + j, c1 = c0 + half;
-        float a = 0.f, b = 0.f;
-        for (int s = 0; s < split; ++s) {
-            const float* p = partial + s * slice_stride + row * width;
-            a += p[c0];
-            b += p[c1];
+    const int head = it / per_head, j = (it % per_head) * 4;
+    const int c0 = head * hd + j, c1 = c0 + half;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    const float* p = partial + row * width;
+    for (int s = 0; s < split; ++s) {
+        a += *reinterpret_cast<const f32x4*>(p + s * slice_stride + c0);
+        b += *reinterpret_cast<const f32x4*>(p + s * slice_stride + c1);
+    }
+    if (bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] += bf16_to_f32(bias[c0 + e]);
+            b[e] += bf16_to_f32(bias[c1 + e]);
         }
-        if (bias) {
-            a += bf16_to_f32(bias[c0]);
-            b += bf16_to_f32(bias[c1]);
-        }
-        if (pos < 0) {  // padding row: defined q (zero), no cache write
-            if (head < n_q) {
-                q_out[row * (size_t)(n_q * hd) + c0] = 0;
-                q_out[row * (size_t)(n_q * hd) + c1] = 0;
-            }
-            continue;
-        }
-        if (head < n_q + n_kv) {
-            // positions past the table are the caller's error; clamp so that the read stays in bounds
-            const float2 cs = rope[(size_t)(pos < max_pos ? pos : max_pos - 1) * half + j];
-            const float ra = a * cs.x - b * cs.y;
-            const float rb = b * cs.x + a * cs.y;
-            a = ra;
-            b = rb;
-        }
+    }
+    if (pos < 0 || slot < 0) {  // padding row: defined q (zero), no cache write
         if (head < n_q) {
-            q_out[row * (size_t)(n_q * hd) + c0] = f32_to_bf16(a);
-            q_out[row * (size_t)(n_q * hd) + c1] = f32_to_bf16(b);
-        } else if (head < n_q + n_kv) {
-            const int g = head - n_q;
-            bf16_t* dst = k_pool + (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd;
-            dst[j] = f32_to_bf16(a);
-            dst[j + half] = f32_to_bf16(b);
-        } else {
-            const int g = head - n_q - n_kv;
-            bf16_t* dst = v_pool + ((size_t)page * n_kv + g) * hd * LAPS_PAGE + off;
-            dst[(size_t)j * LAPS_PAGE] = f32_to_bf16(a);
-            dst[(size_t)(j + half) * LAPS_PAGE] = f32_to_bf16(b);
+            const u32x2 z = {0u, 0u};
+            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c0) = z;
+            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c1) = z;
+        }
+        return;
+    }
+    if (head < n_q + n_kv) {
+        // positions past the table are the caller's error; clamp so that the read stays in bounds
+        const float2* cs = rope + (size_t)(pos < max_pos ? pos : max_pos - 1) * half + j;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float2 t = cs[e];
+            const float ra = a[e] * t.x - b[e] * t.y;
+            const float rb = b[e] * t.x + a[e] * t.y;
+            a[e] = ra;
+            b[e] = rb;
+        }
+    }
+    u32x2 wa, wb;
+    wa.x = pack_bf16x2(a.x, a.y);
+    wa.y = pack_bf16x2(a.z, a.w);
+    wb.x = pack_bf16x2(b.x, b.y);
+    wb.y = pack_bf16x2(b.z, b.w);
+    const int page = slot / LAPS_PAGE, off = slot % LAPS_PAGE;
+    if (head < n_q) {
+        *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c0) = wa;
+        *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c1) = wb;
+    } else if (head < n_q + n_kv) {
+        const int g = head - n_q;
+        bf16_t* dst = k_pool + (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd;
+        *reinterpret_cast<u32x2*>(dst + j) = wa;
+        *reinterpret_cast<u32x2*>(dst + j + half) = wb;
+    } else {
+        const int g = head - n_q - n_kv;
+        bf16_t* dst = v_pool + ((size_t)page * n_kv + g) * hd * LAPS_PAGE + off;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dst[(size_t)(j + e) * LAPS_PAGE] = f32_to_bf16(a[e]);
+            dst[(size_t)(j + half + e) * LAPS_PAGE] = f32_to_bf16(b[e]);
         }
     }
 }
@@ -201,7 +244,9 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_swiglu_kernel(const float* __
                                                                   int inter) {
     const size_t row = blockIdx.x;
     const int width = 2 * inter;
-    for (int c4 = threadIdx.x; c4 < inter / 4; c4 += ROW_THREADS) {
+    {
+        const int c4 = blockIdx.y * ROW_THREADS + threadIdx.x;
+        if (c4 >= inter / 4) return;
         const int c = c4 * 4;
         const int blk = c / 32, in = c % 32;
         const size_t gcol = (size_t)blk * 64 + in;
@@ -302,14 +347,14 @@ int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, 
 int laps_launch_epi_resid(const float* partial, int split, const float* resid, float* x_out, const bf16_t* ln_w,
                           bf16_t* r_out, int rows, int d, float eps, hipStream_t s) {
     const size_t stride = (size_t)rows * d;
-    if (d <= 4 * ROW_THREADS * 2)
-        hipLaunchKernelGGL(epi_resid_kernel<2>, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, resid, x_out,
-                           ln_w, r_out, d, eps);
-    else if (d <= 4 * ROW_THREADS * 8)
-        hipLaunchKernelGGL(epi_resid_kernel<8>, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, resid, x_out,
-                           ln_w, r_out, d, eps);
+    if (d <= 4 * RESID_THREADS * 1)
+        hipLaunchKernelGGL(epi_resid_kernel<1>, dim3(rows), dim3(RESID_THREADS), 0, s, partial, split, stride, resid,
+                           x_out, ln_w, r_out, d, eps);
+    else if (d <= 4 * RESID_THREADS * 4)
+        hipLaunchKernelGGL(epi_resid_kernel<4>, dim3(rows), dim3(RESID_THREADS), 0, s, partial, split, stride, resid,
+                           x_out, ln_w, r_out, d, eps);
     else {
-        laps_set_error("hidden size %d too large for the fused residual + norm kernel", d);
+        laps_set_error("row width %d too large for the fused residual + norm kernel (max %d)", d, 4 * RESID_THREADS * 4);
         return LAPS_EINVAL;
     }
     LAPS_LAUNCH_CHECK();
@@ -320,15 +365,18 @@ int laps_launch_epi_qkv(const float* partial, int split, const bf16_t* bias, con
                         const float2* rope, int max_pos, bf16_t* q_out, bf16_t* k_pool, bf16_t* v_pool, int rows,
                         int n_q, int n_kv, int hd, hipStream_t s) {
     const size_t stride = (size_t)rows * (n_q + 2 * n_kv) * hd;
-    hipLaunchKernelGGL(epi_qkv_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, bias, tok_pos,
-                       tok_slot, rope, max_pos, q_out, k_pool, v_pool, n_q, n_kv, hd);
+    const int n_items = (n_q + 2 * n_kv) * (hd / 8);
+    hipLaunchKernelGGL(epi_qkv_kernel, dim3(rows, (n_items + ROW_THREADS - 1) / ROW_THREADS), dim3(ROW_THREADS), 0, s,
+                       partial, split, stride, bias, tok_pos, tok_slot, rope, max_pos, q_out, k_pool, v_pool, n_q, n_kv,
+                       hd);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
 
 int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, hipStream_t s) {
     const size_t stride = (size_t)rows * 2 * inter;
-    hipLaunchKernelGGL(epi_swiglu_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, partial, split, stride, act, inter);
+    hipLaunchKernelGGL(epi_swiglu_kernel, dim3(rows, (inter / 4 + ROW_THREADS - 1) / ROW_THREADS), dim3(ROW_THREADS), 0,
+                       s, partial, split, stride, act, inter);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }

@@ -3,20 +3,21 @@
 //   C[M,N] = A[M,K] * W[N,K]^T        A: activations (row-major, K contiguous)
 //                                      W: weights in [out, in] order (row-major, K contiguous)
 //
-// Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of one row) is
-// one 16-byte read.  A workgroup owns a BM x BN output tile and one K slice; the K loop moves
-// 64-wide slabs HBM -> registers -> LDS (double buffered, one barrier per slab) while the
-// previous slab feeds the matrix cores.
+// Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of one row) is one
+// 16-byte read.  A workgroup owns a BM x BN output tile and one K slice.  The K loop moves 64-wide
+// slabs HBM -> registers -> LDS (two LDS buffers) and is software-pipelined by hand:
+//   * fragments of k-step kk+1 are read from LDS into a second register set before the MFMAs of
+//     k-step kk are issued, so LDS latency hides behind 8..16 MFMAs;
+//   * the registers holding slab kt+1 are written to the other LDS buffer in the middle of slab kt
+//     and immediately reloaded with slab kt+2 from HBM (about 1.75 slabs of prefetch distance);
+//   * the one barrier per slab sits in the middle of the last k-step's MFMAs and waits on LDS
+//     traffic only, never on the HBM loads in flight.
+// Epilogues: raw K-slice partial sums (split-K, reduced deterministically by the row kernels in
+// elementwise.hip), residual add (fp32 out), or SwiGLU on interleaved gate/up columns (bf16 out).
 //
-// Two tile shapes:
-//   cfg 0  128x128, 4 waves of 64x64   - weight streaming for M <= 128 (bandwidth-bound):
-//                                         many K slices so that >= 2 workgroups per CU keep
-//                                         loads in flight;
-//   cfg 1  256x256, 4 waves of 128x128 - compute-bound shapes: 16 MFMAs per 8 LDS fragment
-//                                         reads, all 256 accumulator registers in use.
-// Workgroup ids are remapped so that each of the 8 XCDs (workgroups are dealt to them round-
-// robin) gets a contiguous range of tiles, walked M-fastest in groups of 8 row tiles: the
-// workgroups sharing a weight panel sit on one XCD and hit its L2.
+// Workgroup ids are remapped so that each of the 8 XCDs (workgroups are dealt to them round-robin)
+// gets a contiguous range of tiles, walked M-fastest in groups of 8 row tiles: the workgroups
+// sharing a weight panel sit on one XCD and hit its L2.
 #include "laps_internal.h"
 
 namespace {
@@ -32,6 +33,9 @@ constexpr int GROUP_M = 8;
 // chunk) and slab writes (8 lanes = one row, all chunks).
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row & 7) ^ ((row >> 3) & 1)); }
 
+// LDS-only barrier: waits for this wave's LDS reads/writes, not for global loads in flight.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int BM, int BN, int WM, int WN>
 struct Traits {
     static constexpr int NT = WM * WN * 64;
@@ -40,6 +44,7 @@ struct Traits {
     static constexpr int A_LOADS = BM * CHUNKS / NT, B_LOADS = BN * CHUNKS / NT;
     static constexpr int LDS_BYTES = 2 * (BM + BN) * BK * 2;
     static_assert(BM * CHUNKS % NT == 0 && BN * CHUNKS % NT == 0, "tile rows must divide over threads");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
 };
 
 struct TileCoord {
@@ -65,20 +70,27 @@ __device__ __forceinline__ TileCoord map_block(int bid, int tiles_m, int tiles_n
     return c;
 }
 
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_partial_kernel(const bf16_t* __restrict__ A,
-                                                                   const bf16_t* __restrict__ W,
-                                                                   float* __restrict__ P, int M, int N, int K,
-                                                                   int split, int kps, int tiles_m, int tiles_n) {
+struct GemmArgs {
+    const bf16_t* A;
+    const bf16_t* W;
+    int M, N, K, split, kps, tiles_m, tiles_n;
+    float* out_f32;        // EPI_PARTIAL: [split][M][N]; EPI_RESID: [M][N]
+    const float* resid;    // EPI_RESID: [M][N] (may alias out_f32)
+    bf16_t* out_bf16;      // EPI_SWIGLU: [M][N/2]
+};
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     using T = Traits<BM, BN, WM, WN>;
     extern __shared__ __align__(16) unsigned char smem[];
-    u32x4* As = reinterpret_cast<u32x4*>(smem);     // [2][BM][CHUNKS]
-    u32x4* Bs = As + 2 * BM * CHUNKS;               // [2][BN][CHUNKS]
+    u32x4* As = reinterpret_cast<u32x4*>(smem);  // [2][BM][CHUNKS]
+    u32x4* Bs = As + 2 * BM * CHUNKS;            // [2][BN][CHUNKS]
 
-    const TileCoord tc = map_block(blockIdx.x, tiles_m, tiles_n, split);
+    const int M = g.M, N = g.N, K = g.K;
+    const TileCoord tc = map_block(blockIdx.x, g.tiles_m, g.tiles_n, g.split);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
-    const int kbeg = tc.ks * kps;
-    const int kend = (kbeg + kps < K) ? (kbeg + kps) : K;
+    const int kbeg = tc.ks * g.kps;
+    const int kend = (kbeg + g.kps < K) ? (kbeg + g.kps) : K;
     const int KT = (kend - kbeg) / BK;
 
     const int tid = threadIdx.x;
@@ -94,15 +106,22 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_partial_kernel(const bf16_t*
     for (int i = 0; i < T::A_LOADS; ++i) {
         const int c = tid + i * T::NT, row = c / CHUNKS, kc = c % CHUNKS;
         const int gr = (m0 + row < M) ? (m0 + row) : (M - 1);  // clamp: rows past M are never stored
-        ag[i] = reinterpret_cast<const u32x4*>(A + (size_t)gr * K + kbeg) + kc;
+        ag[i] = reinterpret_cast<const u32x4*>(g.A + (size_t)gr * K + kbeg) + kc;
         a_dst[i] = row * CHUNKS + swz(row, kc);
     }
 #pragma unroll
     for (int i = 0; i < T::B_LOADS; ++i) {
         const int c = tid + i * T::NT, row = c / CHUNKS, kc = c % CHUNKS;
-        bg[i] = reinterpret_cast<const u32x4*>(W + (size_t)(n0 + row) * K + kbeg) + kc;
+        bg[i] = reinterpret_cast<const u32x4*>(g.W + (size_t)(n0 + row) * K + kbeg) + kc;
         b_dst[i] = row * CHUNKS + swz(row, kc);
     }
+    // fragment read offsets (in 16-byte chunks) inside one LDS buffer, per k-step
+    int a_src[T::MI], b_src[T::NI];
+#pragma unroll
+    for (int mi = 0; mi < T::MI; ++mi) a_src[mi] = (wm * T::WTM + mi * 32 + lrow) * CHUNKS;
+#pragma unroll
+    for (int ni = 0; ni < T::NI; ++ni) b_src[ni] = (wn * T::WTN + ni * 32 + lrow) * CHUNKS;
+    const int a_sw = (lrow & 7) ^ ((lrow >> 3) & 1);  // rows differ by multiples of 32: same swizzle key
 
     f32x16 acc[T::MI][T::NI];
 #pragma unroll
@@ -112,150 +131,290 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_partial_kernel(const bf16_t*
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    u32x4 ra[T::A_LOADS], rb[T::B_LOADS];
+    u32x4 rr[T::A_LOADS + T::B_LOADS];  // slab staging registers: A chunks then B chunks
+    bf16x8 fa[2][T::MI], fb[2][T::NI];
+    constexpr int NM = T::MI * T::NI;            // MFMAs per k-step
+    constexpr int NF = T::MI + T::NI;            // fragment reads per k-step
+    constexpr int NC = T::A_LOADS + T::B_LOADS;  // slab copy operations (global load + LDS store pairs)
+    constexpr int NC0 = (NC + 1) / 2;            // copies handled in k-step 0; the rest in k-step 1
+
+    auto gload_one = [&](int i, int kt) {
+        if (i < T::A_LOADS) rr[i] = ag[i][kt * CHUNKS];
+        else rr[i] = bg[i - T::A_LOADS][kt * CHUNKS];
+    };
+    auto lstore_one = [&](int i, int buf) {
+        if (i < T::A_LOADS) As[buf * BM * CHUNKS + a_dst[i]] = rr[i];
+        else Bs[buf * BN * CHUNKS + b_dst[i - T::A_LOADS]] = rr[i];
+    };
+    auto fload_one = [&](int i, int buf, int kk, int set) {
+        const int ch = (kk * 2 + lk) ^ a_sw;
+        if (i < T::MI) fa[set][i] = __builtin_bit_cast(bf16x8, As[buf * BM * CHUNKS + a_src[i] + ch]);
+        else fb[set][i - T::MI] = __builtin_bit_cast(bf16x8, Bs[buf * BN * CHUNKS + b_src[i - T::MI] + ch]);
+    };
+    auto mma_one = [&](int i, int set) {
+        const int mi = i / T::NI, ni = i % T::NI;
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mi], fb[set][ni], acc[mi][ni], 0, 0, 0);
+    };
+
     if (KT > 0) {
 #pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i) ra[i] = ag[i][0];
+        for (int i = 0; i < NC; ++i) gload_one(i, 0);
 #pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i) rb[i] = bg[i][0];
+        for (int i = 0; i < NC; ++i) lstore_one(i, 0);
 #pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i) As[a_dst[i]] = ra[i];
+        for (int i = 0; i < NC; ++i) gload_one(i, KT > 1 ? 1 : 0);
+        lds_barrier();
 #pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i) Bs[b_dst[i]] = rb[i];
+        for (int i = 0; i < NF; ++i) fload_one(i, 0, 0, 0);
     }
-    __syncthreads();
-
+    // One memory operation is slotted behind each MFMA so that the matrix pipe never waits for a
+    // clump of LDS / HBM instructions to issue (one wave per SIMD: nothing else would feed it).
+    //   k-step 0: MFMAs on set 0 | reads of k-step 1 fragments -> set 1 | first half of the slab copy
+    //   k-step 1: MFMAs on set 1 | reads of k-step 2 fragments -> set 0 | second half of the slab copy
+    //   k-step 2: MFMAs on set 0 | reads of k-step 3 fragments -> set 1
+    //   k-step 3: MFMAs on set 1 | barrier half way | reads of the next slab's k-step 0 -> set 0
+    // A slab copy = store staged registers (slab kt+1) to the other LDS buffer, then reload them from
+    // HBM with slab kt+2: one full slab of MFMAs lies between a global load and its use.
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
-        const bool more = (kt + 1 < KT);
-        if (more) {
+        // The tail iterations keep the same instruction stream (no branches in the pipeline): they
+        // re-store and re-load the last slab, which nothing reads afterwards.
+        const int kt2 = (kt + 2 < KT) ? kt + 2 : KT - 1;
 #pragma unroll
-            for (int i = 0; i < T::A_LOADS; ++i) ra[i] = ag[i][(kt + 1) * CHUNKS];
+        for (int i = 0; i < NM; ++i) {
+            mma_one(i, 0);
 #pragma unroll
-            for (int i = 0; i < T::B_LOADS; ++i) rb[i] = bg[i][(kt + 1) * CHUNKS];
-        }
-        const u32x4* as = As + cur * BM * CHUNKS;
-        const u32x4* bs = Bs + cur * BN * CHUNKS;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[T::MI], bfr[T::NI];
-#pragma unroll
-            for (int mi = 0; mi < T::MI; ++mi) {
-                const int row = wm * T::WTM + mi * 32 + lrow;
-                af[mi] = __builtin_bit_cast(bf16x8, as[row * CHUNKS + swz(row, kk * 2 + lk)]);
+            for (int o = i; o < NF + NC0; o += NM) {
+                if (o < NF) fload_one(o, cur, 1, 1);
+                else {
+                    lstore_one(o - NF, cur ^ 1);
+                    gload_one(o - NF, kt2);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
-            for (int ni = 0; ni < T::NI; ++ni) {
-                const int row = wn * T::WTN + ni * 32 + lrow;
-                bfr[ni] = __builtin_bit_cast(bf16x8, bs[row * CHUNKS + swz(row, kk * 2 + lk)]);
+        for (int i = 0; i < NM; ++i) {
+            mma_one(i, 1);
+#pragma unroll
+            for (int o = i; o < NF + (NC - NC0); o += NM) {
+                if (o < NF) fload_one(o, cur, 2, 0);
+                else {
+                    lstore_one(NC0 + o - NF, cur ^ 1);
+                    gload_one(NC0 + o - NF, kt2);
+                }
             }
-#pragma unroll
-            for (int mi = 0; mi < T::MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < T::NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
-            u32x4* ad = As + (cur ^ 1) * BM * CHUNKS;
-            u32x4* bd = Bs + (cur ^ 1) * BN * CHUNKS;
 #pragma unroll
-            for (int i = 0; i < T::A_LOADS; ++i) ad[a_dst[i]] = ra[i];
+        for (int i = 0; i < NM; ++i) {
+            mma_one(i, 0);
 #pragma unroll
-            for (int i = 0; i < T::B_LOADS; ++i) bd[b_dst[i]] = rb[i];
+            for (int o = i; o < NF; o += NM) fload_one(o, cur, 3, 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
+        constexpr int NH = NM / 2;
+#pragma unroll
+        for (int i = 0; i < NH; ++i) mma_one(i, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = NH; i < NM; ++i) {
+            mma_one(i, 1);
+#pragma unroll
+            for (int o = i - NH; o < NF; o += NM - NH) fload_one(o, cur ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // accumulator layout of the 32x32 MFMA: lane -> column (lane & 31); register r -> row
     // 8*(r/4) + 4*(lane/32) + r%4
-    float* out = P + (size_t)tc.ks * M * N;
+    if constexpr (EPI == EPI_PARTIAL || EPI == EPI_RESID) {
+        float* out = g.out_f32 + (EPI == EPI_PARTIAL ? (size_t)tc.ks * M * N : (size_t)0);
 #pragma unroll
-    for (int mi = 0; mi < T::MI; ++mi)
+        for (int mi = 0; mi < T::MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < T::NI; ++ni) {
-            const int n = n0 + wn * T::WTN + ni * 32 + lrow;
+            for (int ni = 0; ni < T::NI; ++ni) {
+                const int n = n0 + wn * T::WTN + ni * 32 + lrow;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (m < M) out[(size_t)m * N + n] = acc[mi][ni][r];
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                    if (m < M) {
+                        const size_t o = (size_t)m * N + n;
+                        out[o] = (EPI == EPI_RESID) ? g.resid[o] + acc[mi][ni][r] : acc[mi][ni][r];
+                    }
+                }
             }
-        }
+    } else {  // EPI_SWIGLU: sub-tile 2j holds gate columns, sub-tile 2j+1 the matching up columns
+        static_assert(EPI != EPI_SWIGLU || T::NI % 2 == 0, "SwiGLU epilogue pairs 32-column sub-tiles");
+        const int half_n = N / 2;
+#pragma unroll
+        for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < T::NI / 2; ++j) {
+                const int col = (n0 + wn * T::WTN) / 2 + j * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                    if (m < M) {
+                        const float gt = acc[mi][2 * j][r], up = acc[mi][2 * j + 1][r];
+                        g.out_bf16[(size_t)m * half_n + col] = f32_to_bf16(gt / (1.f + __expf(-gt)) * up);
+                    }
+                }
+            }
+    }
 }
 
-template <int BM, int BN, int WM, int WN>
-int launch_cfg(const GemmPlan& p, const bf16_t* a, const bf16_t* w, float* partial, int m, int n, int k,
-               hipStream_t s) {
+template <int BM, int BN, int WM, int WN, int EPI>
+int launch_tile(const GemmArgs& a, hipStream_t s) {
     using T = Traits<BM, BN, WM, WN>;
-    auto kern = gemm_partial_kernel<BM, BN, WM, WN>;
+    auto kern = gemm_kernel<BM, BN, WM, WN, EPI>;
     static bool attr_set = false;  // per instantiation; idempotent, so a race only repeats the call
     if (!attr_set) {
-        LAPS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES));
+        LAPS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     T::LDS_BYTES));
         attr_set = true;
     }
-    const int tiles_m = (m + BM - 1) / BM, tiles_n = n / BN;
-    const int grid = tiles_m * tiles_n * p.split;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, w, partial, m, n, k, p.split,
-                       p.k_per_split, tiles_m, tiles_n);
+    const int grid = a.tiles_m * a.tiles_n * a.split;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
 
+struct TileDef {
+    int bm, bn;
+    double eff;  // relative MFMA efficiency of the tile shape (operand reuse), 256x256 = 1
+};
+// index = GemmPlan::cfg
+constexpr TileDef kTiles[] = {
+    {128, 128, 0.70},  // 0: skinny, 4 waves of 64x64
+    {128, 64, 0.50},   // 1: skinny, narrow panels for small N
+    {256, 256, 1.00},  // 2: 4 waves of 128x128
+    {256, 224, 0.93},  // 3: 4 waves of 64x224 (N = 7168 -> 32 column tiles)
+    {256, 160, 0.85},  // 4: 4 waves of 64x160 (N = 5120 -> 32 column tiles)
+};
+
 }  // namespace
 
-GemmPlan laps_gemm_plan(int m, int n, int k, int force_split) {
+// Picks tile shape and K split.  Bandwidth-bound shapes (M <= 128): enough workgroups to keep
+// >= 2 per CU streaming weights while keeping the fp32 partial-sum traffic (2*split*M*N*4 bytes)
+// small against the weight bytes.  Compute-bound shapes: minimise
+//   rounds(tiles*split over 256 CUs) * per-workgroup MFMA time + partial-sum traffic time.
+GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
     GemmPlan p;
-    p.cfg = (m > 128 && n % 256 == 0) ? 1 : 0;
-    const int bm = p.cfg ? 256 : 128, bn = bm;
-    const int tiles = ((m + bm - 1) / bm) * (n / bn);
     const int ksteps = k / BK;
-    int split = 1;
-    if (force_split > 0) {
-        split = force_split;
-    } else if (p.cfg == 0) {
-        // bandwidth-bound: at least two workgroups per CU, each with >= 8 slabs of K
-        split = (512 + tiles - 1) / tiles;
-        const int cap = ksteps / 8 > 1 ? ksteps / 8 : 1;
-        if (split > cap) split = cap;
-    } else {
-        // compute-bound: smallest split whose last wave of workgroups is not mostly idle
-        double best = -1.0;
+    auto finish = [&](int cfg, int split) {
+        if (split > ksteps) split = ksteps;
+        if (split < 1) split = 1;
+        const int per = (ksteps + split - 1) / split;
+        p.cfg = cfg;
+        p.k_per_split = per * BK;
+        p.split = (ksteps + per - 1) / per;
+        p.epi = (p.split == 1) ? want_epi : EPI_PARTIAL;
+        return p;
+    };
+    if (m <= 128) {
+        // 128-wide panels for wide outputs and for the fused SwiGLU (gate/up pairs must share a wave
+        // tile); 64-wide panels give the small projections twice as many workgroups per K slice
+        int cfg = (n % 128 == 0 && (n >= 16384 || want_epi == EPI_SWIGLU)) ? 0 : 1;
+        if (n % 64 != 0) cfg = 0;  // rejected at launch
+        if (cfg == 1 && want_epi == EPI_SWIGLU) want_epi = EPI_PARTIAL;
+        const int tiles = n / kTiles[cfg].bn;
+        int split = force_split;
+        if (split <= 0) {
+            split = 1;
+            if (tiles < 400) {
+                split = (448 + tiles - 1) / tiles;
+                const int cap = ksteps / 8 > 1 ? ksteps / 8 : 1;
+                if (split > cap) split = cap;
+            }
+        }
+        return finish(cfg, split);
+    }
+    // compute-bound
+    double best = 1e30;
+    int best_cfg = 2, best_split = 1;
+    for (int cfg = 2; cfg <= 4; ++cfg) {
+        const TileDef& t = kTiles[cfg];
+        if (n % t.bn != 0) continue;
+        if (want_epi == EPI_SWIGLU && cfg != 2) continue;
+        const int tiles = ((m + t.bm - 1) / t.bm) * (n / t.bn);
         for (int s = 1; s <= 8; ++s) {
+            if (force_split > 0 && s != force_split) continue;
             if (s > 1 && ksteps / s < 16) break;
-            const int wgs = tiles * s;
-            const int waves = (wgs + 255) / 256;
-            const double eff = (double)wgs / (waves * 256.0);
-            if (eff > best + 0.04) {
-                best = eff;
-                split = s;
+            const long wgs = (long)tiles * s;
+            const long rounds = (wgs + 255) / 256;
+            const double wg_flops = 2.0 * t.bm * t.bn * (double)k / s;
+            const double t_mma = rounds * wg_flops / (2.5e15 / 256 * 0.62 * t.eff);
+            const double t_part = s > 1 ? (2.0 * s * m * (double)n * 4) / 4.0e12 + 4e-6 : 0.0;
+            const double cost = t_mma + t_part;
+            if (cost < best) {
+                best = cost;
+                best_cfg = cfg;
+                best_split = s;
             }
         }
     }
-    if (split > ksteps) split = ksteps;
-    if (split < 1) split = 1;
-    const int per = (ksteps + split - 1) / split;
-    p.k_per_split = per * BK;
-    p.split = (ksteps + per - 1) / per;
-    return p;
+    if (best >= 1e30) {  // no wide tile divides n: fall back to the 128- or 64-wide panels
+        const int cfg = (n % 128 == 0) ? 0 : 1;
+        if (cfg == 1 && want_epi == EPI_SWIGLU) want_epi = EPI_PARTIAL;
+        return finish(cfg, force_split > 0 ? force_split : 1);
+    }
+    return finish(best_cfg, best_split);
 }
 
 size_t laps_gemm_partial_bytes(int m, int n, int k) {
-    const GemmPlan p = laps_gemm_plan(m, n, k, 0);
-    return (size_t)p.split * m * n * sizeof(float);
+    // upper bound over the epilogue kinds the layer driver may request
+    size_t b = 0;
+    for (int e = 0; e < 3; ++e) {
+        const GemmPlan p = laps_gemm_plan(m, n, k, 0, e);
+        const size_t t = p.split > 1 ? (size_t)p.split * m * n * sizeof(float) : 0;
+        b = t > b ? t : b;
+    }
+    // QKV always goes through the partial buffer (its epilogue is a separate kernel)
+    const size_t one = (size_t)m * n * sizeof(float);
+    return b > one ? b : one;
 }
 
-int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, float* partial, int m, int n, int k,
-                     hipStream_t s) {
-    if (m < 1 || n < 128 || k < BK || k % BK != 0 || n % 128 != 0) {
-        laps_set_error("gemm: unsupported shape m=%d n=%d k=%d (need k %% 64 == 0, n %% 128 == 0)", m, n, k);
+int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
+                     const float* resid, bf16_t* out_bf16, hipStream_t s) {
+    if (m < 1 || n < 64 || k < BK || k % BK != 0 || p.cfg < 0 || p.cfg > 4 || n % kTiles[p.cfg].bn != 0) {
+        laps_set_error("gemm: unsupported shape m=%d n=%d k=%d for tile %d", m, n, k, p.cfg);
         return LAPS_EINVAL;
     }
-    if (p.cfg == 1) {
-        if (n % 256 != 0) {
-            laps_set_error("gemm: 256-wide tile needs n %% 256 == 0 (n=%d)", n);
-            return LAPS_EINVAL;
-        }
-        return launch_cfg<256, 256, 2, 2>(p, a, w, partial, m, n, k, s);
+    if (p.epi != EPI_PARTIAL && p.split != 1) {
+        laps_set_error("gemm: fused epilogue needs a single K slice");
+        return LAPS_EINVAL;
     }
-    return launch_cfg<128, 128, 2, 2>(p, a, w, partial, m, n, k, s);
+    GemmArgs g;
+    g.A = a;
+    g.W = w;
+    g.M = m;
+    g.N = n;
+    g.K = k;
+    g.split = p.split;
+    g.kps = p.k_per_split;
+    g.tiles_m = (m + kTiles[p.cfg].bm - 1) / kTiles[p.cfg].bm;
+    g.tiles_n = n / kTiles[p.cfg].bn;
+    g.out_f32 = out_f32;
+    g.resid = resid;
+    g.out_bf16 = out_bf16;
+    switch (p.cfg * 4 + p.epi) {
+        case 0 * 4 + EPI_PARTIAL: return launch_tile<128, 128, 2, 2, EPI_PARTIAL>(g, s);
+        case 0 * 4 + EPI_RESID: return launch_tile<128, 128, 2, 2, EPI_RESID>(g, s);
+        case 0 * 4 + EPI_SWIGLU: return launch_tile<128, 128, 2, 2, EPI_SWIGLU>(g, s);
+        case 1 * 4 + EPI_PARTIAL: return launch_tile<128, 64, 2, 2, EPI_PARTIAL>(g, s);
+        case 1 * 4 + EPI_RESID: return launch_tile<128, 64, 2, 2, EPI_RESID>(g, s);
+        case 2 * 4 + EPI_PARTIAL: return launch_tile<256, 256, 2, 2, EPI_PARTIAL>(g, s);
+        case 2 * 4 + EPI_RESID: return launch_tile<256, 256, 2, 2, EPI_RESID>(g, s);
+        case 2 * 4 + EPI_SWIGLU: return launch_tile<256, 256, 2, 2, EPI_SWIGLU>(g, s);
+        case 3 * 4 + EPI_PARTIAL: return launch_tile<256, 224, 4, 1, EPI_PARTIAL>(g, s);
+        case 3 * 4 + EPI_RESID: return launch_tile<256, 224, 4, 1, EPI_RESID>(g, s);
+        case 4 * 4 + EPI_PARTIAL: return launch_tile<256, 160, 4, 1, EPI_PARTIAL>(g, s);
+        case 4 * 4 + EPI_RESID: return launch_tile<256, 160, 4, 1, EPI_RESID>(g, s);
+        default: break;
+    }
+    laps_set_error("gemm: no kernel for tile %d with epilogue %d", p.cfg, p.epi);
+    return LAPS_EINVAL;
 }

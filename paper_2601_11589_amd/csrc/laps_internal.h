@@ -44,16 +44,19 @@ void laps_set_error(const char* fmt, ...);
 // C = A[M,K] * W[N,K]^T, bf16 operands, fp32 accumulation, K-split into `split` slices.
 enum GemmEpi {
     EPI_PARTIAL = 0,  // out_f32[split][M][N] raw partial sums
+    EPI_RESID = 1,    // out_f32[M][N] = resid[M][N] + C              (single K slice only)
+    EPI_SWIGLU = 2,   // out_bf16[M][N/2] = silu(gate) * up on interleaved columns (single K slice only)
 };
 struct GemmPlan {
-    int cfg;        // 0: 128x128 tile (skinny / bandwidth-bound), 1: 256x256 tile
-    int split;      // K slices
+    int cfg;          // tile shape index (see kTiles in gemm.hip)
+    int split;        // K slices
     int k_per_split;  // multiple of 64
+    int epi;          // epilogue the launch will apply: the requested one if split == 1, else EPI_PARTIAL
 };
-GemmPlan laps_gemm_plan(int m, int n, int k, int force_split);
+GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi);
 size_t laps_gemm_partial_bytes(int m, int n, int k);
-int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, float* partial, int m, int n, int k,
-                     hipStream_t s);
+int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
+                     const float* resid, bf16_t* out_bf16, hipStream_t s);
 
 // ----------------------------------------------------------------------------- element-wise / epilogues
 int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s);
