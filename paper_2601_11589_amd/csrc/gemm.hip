@@ -79,7 +79,11 @@ struct GemmArgs {
     bf16_t* out_bf16;      // EPI_SWIGLU: [M][N/2]
 };
 
-template <int BM, int BN, int WM, int WN, int EPI>
+// WS = number of register sets that stage slabs: WS slabs (A and W chunks alike - loads return in
+// issue order, so a shallower A stream would throttle the W stream) are in flight per workgroup.
+// WS > 1 is for the bandwidth-bound skinny shapes; the K loop is then unrolled WS times so every set
+// index is static, and the K slice must hold a multiple of WS slabs.
+template <int BM, int BN, int WM, int WN, int EPI, int WS>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     using T = Traits<BM, BN, WM, WN>;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -93,6 +97,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     const int kend = (kbeg + g.kps < K) ? (kbeg + g.kps) : K;
     const int KT = (kend - kbeg) / BK;
 
+    constexpr bool NT = (BM <= 128);  // skinny tiles only
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -131,100 +136,116 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    u32x4 rr[T::A_LOADS + T::B_LOADS];  // slab staging registers: A chunks then B chunks
+    u32x4 rra[WS][T::A_LOADS];   // staged A slabs: slab j lives in set j % WS
+    u32x4 rrb[WS][T::B_LOADS];   // staged W slabs, same rule
     bf16x8 fa[2][T::MI], fb[2][T::NI];
     constexpr int NM = T::MI * T::NI;            // MFMAs per k-step
     constexpr int NF = T::MI + T::NI;            // fragment reads per k-step
     constexpr int NC = T::A_LOADS + T::B_LOADS;  // slab copy operations (global load + LDS store pairs)
     constexpr int NC0 = (NC + 1) / 2;            // copies handled in k-step 0; the rest in k-step 1
 
-    auto gload_one = [&](int i, int kt) {
-        if (i < T::A_LOADS) rr[i] = ag[i][kt * CHUNKS];
-        else rr[i] = bg[i - T::A_LOADS][kt * CHUNKS];
+    auto clampk = [&](int kt) { return kt < KT ? kt : KT - 1; };  // tail: reload a valid slab, never used
+    // copy op i of the slab pipeline: i < A_LOADS moves an A chunk, else a W chunk held in set `ws`
+    auto gload_one = [&](int i, int kt, int ws) {
+        if (i < T::A_LOADS) rra[ws][i] = ag[i][clampk(kt) * CHUNKS];
+        else {
+            // weights are read once: streaming (non-temporal) loads keep them from evicting the A slabs,
+            // which every workgroup on the CU and on the XCD re-reads, out of L1 / L2
+            const u32x4* src = bg[i - T::A_LOADS] + clampk(kt) * CHUNKS;
+            rrb[ws][i - T::A_LOADS] = NT ? __builtin_nontemporal_load(src) : *src;
+        }
     };
-    auto lstore_one = [&](int i, int buf) {
-        if (i < T::A_LOADS) As[buf * BM * CHUNKS + a_dst[i]] = rr[i];
-        else Bs[buf * BN * CHUNKS + b_dst[i - T::A_LOADS]] = rr[i];
+    auto lstore_one = [&](int i, int buf, int ws) {
+        if (i < T::A_LOADS) As[buf * BM * CHUNKS + a_dst[i]] = rra[ws][i];
+        else Bs[buf * BN * CHUNKS + b_dst[i - T::A_LOADS]] = rrb[ws][i - T::A_LOADS];
     };
+    // order of need by the MFMA sequence (mi-major): A row block 0, every B column block, remaining A
     auto fload_one = [&](int i, int buf, int kk, int set) {
         const int ch = (kk * 2 + lk) ^ a_sw;
-        if (i < T::MI) fa[set][i] = __builtin_bit_cast(bf16x8, As[buf * BM * CHUNKS + a_src[i] + ch]);
-        else fb[set][i - T::MI] = __builtin_bit_cast(bf16x8, Bs[buf * BN * CHUNKS + b_src[i - T::MI] + ch]);
+        if (i == 0) fa[set][0] = __builtin_bit_cast(bf16x8, As[buf * BM * CHUNKS + a_src[0] + ch]);
+        else if (i <= T::NI) fb[set][i - 1] = __builtin_bit_cast(bf16x8, Bs[buf * BN * CHUNKS + b_src[i - 1] + ch]);
+        else fa[set][i - T::NI] = __builtin_bit_cast(bf16x8, As[buf * BM * CHUNKS + a_src[i - T::NI] + ch]);
     };
     auto mma_one = [&](int i, int set) {
         const int mi = i / T::NI, ni = i % T::NI;
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mi], fb[set][ni], acc[mi][ni], 0, 0, 0);
     };
 
-    if (KT > 0) {
+    // prologue: slab 0 through the registers into LDS buffer 0, then A slab 1 and W slabs 1..WS in flight
 #pragma unroll
-        for (int i = 0; i < NC; ++i) gload_one(i, 0);
+    for (int i = 0; i < NC; ++i) gload_one(i, 0, 0);
 #pragma unroll
-        for (int i = 0; i < NC; ++i) lstore_one(i, 0);
+    for (int i = 0; i < NC; ++i) lstore_one(i, 0, 0);
 #pragma unroll
-        for (int i = 0; i < NC; ++i) gload_one(i, KT > 1 ? 1 : 0);
-        lds_barrier();
+    for (int w = 1; w <= WS; ++w)
 #pragma unroll
-        for (int i = 0; i < NF; ++i) fload_one(i, 0, 0, 0);
-    }
+        for (int i = 0; i < NC; ++i) gload_one(i, w, w % WS);
+    lds_barrier();
+#pragma unroll
+    for (int i = 0; i < NF; ++i) fload_one(i, 0, 0, 0);
+
     // One memory operation is slotted behind each MFMA so that the matrix pipe never waits for a
     // clump of LDS / HBM instructions to issue (one wave per SIMD: nothing else would feed it).
     //   k-step 0: MFMAs on set 0 | reads of k-step 1 fragments -> set 1 | first half of the slab copy
     //   k-step 1: MFMAs on set 1 | reads of k-step 2 fragments -> set 0 | second half of the slab copy
     //   k-step 2: MFMAs on set 0 | reads of k-step 3 fragments -> set 1
     //   k-step 3: MFMAs on set 1 | barrier half way | reads of the next slab's k-step 0 -> set 0
-    // A slab copy = store staged registers (slab kt+1) to the other LDS buffer, then reload them from
-    // HBM with slab kt+2: one full slab of MFMAs lies between a global load and its use.
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        // The tail iterations keep the same instruction stream (no branches in the pipeline): they
-        // re-store and re-load the last slab, which nothing reads afterwards.
-        const int kt2 = (kt + 2 < KT) ? kt + 2 : KT - 1;
+    // A slab copy = store the staged slab kt+1 to the other LDS buffer, then reload the set just freed
+    // with slab kt+1+WS from HBM.  The tail iterations keep the same
+    // instruction stream (no branches in the pipeline): they re-store and re-load the last slab, which
+    // nothing reads afterwards.
+    for (int kt0 = 0; kt0 < KT; kt0 += WS) {
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            mma_one(i, 0);
+        for (int u = 0; u < WS; ++u) {
+            const int kt = kt0 + u;
+            const int cur = (WS == 1) ? (kt & 1) : (u & 1);  // WS is 1 or even
+            const int ws = (u + 1) % WS;                     // set holding W slab kt+1
 #pragma unroll
-            for (int o = i; o < NF + NC0; o += NM) {
-                if (o < NF) fload_one(o, cur, 1, 1);
-                else {
-                    lstore_one(o - NF, cur ^ 1);
-                    gload_one(o - NF, kt2);
+            for (int i = 0; i < NM; ++i) {
+                mma_one(i, 0);
+#pragma unroll
+                for (int o = i; o < NF + NC0; o += NM) {
+                    if (o < NF) fload_one(o, cur, 1, 1);
+                    else {
+                        lstore_one(o - NF, cur ^ 1, ws);
+                        gload_one(o - NF, kt + 1 + WS, ws);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-        }
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            mma_one(i, 1);
+            for (int i = 0; i < NM; ++i) {
+                mma_one(i, 1);
 #pragma unroll
-            for (int o = i; o < NF + (NC - NC0); o += NM) {
-                if (o < NF) fload_one(o, cur, 2, 0);
-                else {
-                    lstore_one(NC0 + o - NF, cur ^ 1);
-                    gload_one(NC0 + o - NF, kt2);
+                for (int o = i; o < NF + (NC - NC0); o += NM) {
+                    if (o < NF) fload_one(o, cur, 2, 0);
+                    else {
+                        lstore_one(NC0 + o - NF, cur ^ 1, ws);
+                        gload_one(NC0 + o - NF, kt + 1 + WS, ws);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                mma_one(i, 0);
+#pragma unroll
+                for (int o = i; o < NF; o += NM) fload_one(o, cur, 3, 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            constexpr int NH = NM / 2;
+#pragma unroll
+            for (int i = 0; i < NH; ++i) mma_one(i, 1);
             __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            mma_one(i, 0);
-#pragma unroll
-            for (int o = i; o < NF; o += NM) fload_one(o, cur, 3, 1);
+            lds_barrier();
             __builtin_amdgcn_sched_barrier(0);
-        }
-        constexpr int NH = NM / 2;
 #pragma unroll
-        for (int i = 0; i < NH; ++i) mma_one(i, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_barrier();
-        __builtin_amdgcn_sched_barrier(0);
+            for (int i = NH; i < NM; ++i) {
+                mma_one(i, 1);
 #pragma unroll
-        for (int i = NH; i < NM; ++i) {
-            mma_one(i, 1);
-#pragma unroll
-            for (int o = i - NH; o < NF; o += NM - NH) fload_one(o, cur ^ 1, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                for (int o = i - NH; o < NF; o += NM - NH) fload_one(o, cur ^ 1, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 
@@ -266,10 +287,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int WS = 1>
 int launch_tile(const GemmArgs& a, hipStream_t s) {
     using T = Traits<BM, BN, WM, WN>;
-    auto kern = gemm_kernel<BM, BN, WM, WN, EPI>;
+    auto kern = gemm_kernel<BM, BN, WM, WN, EPI, WS>;
     static bool attr_set = false;  // per instantiation; idempotent, so a race only repeats the call
     if (!attr_set) {
         LAPS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -288,26 +309,31 @@ struct TileDef {
 };
 // index = GemmPlan::cfg
 constexpr TileDef kTiles[] = {
-    {128, 128, 0.70},  // 0: skinny, 4 waves of 64x64
-    {128, 64, 0.50},   // 1: skinny, narrow panels for small N
+    {128, 128, 0.70},  // 0: skinny fallback (n % 256 != 0), 4 waves of 64x64
+    {128, 64, 0.50},   // 1: skinny fallback (n % 128 != 0)
     {256, 256, 1.00},  // 2: 4 waves of 128x128
     {256, 224, 0.93},  // 3: 4 waves of 64x224 (N = 7168 -> 32 column tiles)
     {256, 160, 0.85},  // 4: 4 waves of 64x160 (N = 5120 -> 32 column tiles)
+    {128, 256, 0.80},  // 5: skinny, 8 waves of 64x64: one workgroup per CU, A slab shared by 256 columns
 };
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 }  // namespace
 
-// Picks tile shape and K split.  Bandwidth-bound shapes (M <= 128): enough workgroups to keep
-// >= 2 per CU streaming weights while keeping the fp32 partial-sum traffic (2*split*M*N*4 bytes)
-// small against the weight bytes.  Compute-bound shapes: minimise
-//   rounds(tiles*split over 256 CUs) * per-workgroup MFMA time + partial-sum traffic time.
+// Picks tile shape and K split.
 GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
     GemmPlan p;
     const int ksteps = k / BK;
     auto finish = [&](int cfg, int split) {
         if (split > ksteps) split = ksteps;
         if (split < 1) split = 1;
-        const int per = (ksteps + split - 1) / split;
+        int per = (ksteps + split - 1) / split;
+        // skinny tiles keep 2 slabs in flight: every K slice must then hold a multiple of 2 slabs
+        p.ws = 1;
+        if (kTiles[cfg].bm == 128 && ksteps % 2 == 0) {
+            per = (per + 1) / 2 * 2;
+            p.ws = 2;
+        }
         p.cfg = cfg;
         p.k_per_split = per * BK;
         p.split = (ksteps + per - 1) / per;
@@ -315,24 +341,24 @@ GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
         return p;
     };
     if (m <= 128) {
-        // 128-wide panels for wide outputs and for the fused SwiGLU (gate/up pairs must share a wave
-        // tile); 64-wide panels give the small projections twice as many workgroups per K slice
-        int cfg = (n % 128 == 0 && (n >= 16384 || want_epi == EPI_SWIGLU)) ? 0 : 1;
-        if (n % 64 != 0) cfg = 0;  // rejected at launch
+        // Bandwidth-bound.  The L2 -> CU path carries W once plus the A slab once per workgroup per
+        // K step, and saturates near 9 TB/s in aggregate: a 256-column tile halves the A share of a
+        // 128-column one.  One workgroup (8 waves) per CU; K is split only to reach ~256 workgroups,
+        // since every extra slice writes and re-reads m*n fp32 partial sums.
+        int cfg = 5;
+        if (n % 256 != 0) cfg = (n % 128 == 0) ? 0 : 1;
         if (cfg == 1 && want_epi == EPI_SWIGLU) want_epi = EPI_PARTIAL;
         const int tiles = n / kTiles[cfg].bn;
         int split = force_split;
         if (split <= 0) {
-            split = 1;
-            if (tiles < 400) {
-                split = (448 + tiles - 1) / tiles;
-                const int cap = ksteps / 8 > 1 ? ksteps / 8 : 1;
-                if (split > cap) split = cap;
-            }
+            split = 256 / tiles;
+            const int cap = ksteps / 8 > 1 ? ksteps / 8 : 1;
+            if (split > cap) split = cap;
         }
         return finish(cfg, split);
     }
-    // compute-bound
+    // compute-bound: minimise rounds(tiles*split over 256 CUs) * per-workgroup MFMA time + the
+    // time to write and re-read the partial sums of a split
     double best = 1e30;
     int best_cfg = 2, best_split = 1;
     for (int cfg = 2; cfg <= 4; ++cfg) {
@@ -379,8 +405,12 @@ size_t laps_gemm_partial_bytes(int m, int n, int k) {
 
 int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
                      const float* resid, bf16_t* out_bf16, hipStream_t s) {
-    if (m < 1 || n < 64 || k < BK || k % BK != 0 || p.cfg < 0 || p.cfg > 4 || n % kTiles[p.cfg].bn != 0) {
+    if (m < 1 || n < 64 || k < BK || k % BK != 0 || p.cfg < 0 || p.cfg >= kNumTiles || n % kTiles[p.cfg].bn != 0) {
         laps_set_error("gemm: unsupported shape m=%d n=%d k=%d for tile %d", m, n, k, p.cfg);
+        return LAPS_EINVAL;
+    }
+    if (p.ws != 1 && (p.k_per_split / BK) % p.ws != 0) {
+        laps_set_error("gemm: K slice of %d slabs is not a multiple of the %d weight stages", p.k_per_split / BK, p.ws);
         return LAPS_EINVAL;
     }
     if (p.epi != EPI_PARTIAL && p.split != 1) {
@@ -400,21 +430,35 @@ int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m,
     g.out_f32 = out_f32;
     g.resid = resid;
     g.out_bf16 = out_bf16;
-    switch (p.cfg * 4 + p.epi) {
-        case 0 * 4 + EPI_PARTIAL: return launch_tile<128, 128, 2, 2, EPI_PARTIAL>(g, s);
-        case 0 * 4 + EPI_RESID: return launch_tile<128, 128, 2, 2, EPI_RESID>(g, s);
-        case 0 * 4 + EPI_SWIGLU: return launch_tile<128, 128, 2, 2, EPI_SWIGLU>(g, s);
-        case 1 * 4 + EPI_PARTIAL: return launch_tile<128, 64, 2, 2, EPI_PARTIAL>(g, s);
-        case 1 * 4 + EPI_RESID: return launch_tile<128, 64, 2, 2, EPI_RESID>(g, s);
-        case 2 * 4 + EPI_PARTIAL: return launch_tile<256, 256, 2, 2, EPI_PARTIAL>(g, s);
-        case 2 * 4 + EPI_RESID: return launch_tile<256, 256, 2, 2, EPI_RESID>(g, s);
-        case 2 * 4 + EPI_SWIGLU: return launch_tile<256, 256, 2, 2, EPI_SWIGLU>(g, s);
-        case 3 * 4 + EPI_PARTIAL: return launch_tile<256, 224, 4, 1, EPI_PARTIAL>(g, s);
-        case 3 * 4 + EPI_RESID: return launch_tile<256, 224, 4, 1, EPI_RESID>(g, s);
-        case 4 * 4 + EPI_PARTIAL: return launch_tile<256, 160, 4, 1, EPI_PARTIAL>(g, s);
-        case 4 * 4 + EPI_RESID: return launch_tile<256, 160, 4, 1, EPI_RESID>(g, s);
+#define LAPS_TILE_CASE(cfg, BM, BN, WM, WN, EPI, WS) \
+    case ((cfg) * 4 + (EPI)) * 8 + (WS): return launch_tile<BM, BN, WM, WN, EPI, WS>(g, s)
+    switch ((p.cfg * 4 + p.epi) * 8 + p.ws) {
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_PARTIAL, 2);
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_RESID, 1);
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_RESID, 2);
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_SWIGLU, 1);
+        LAPS_TILE_CASE(0, 128, 128, 2, 2, EPI_SWIGLU, 2);
+        LAPS_TILE_CASE(1, 128, 64, 2, 2, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(1, 128, 64, 2, 2, EPI_PARTIAL, 2);
+        LAPS_TILE_CASE(1, 128, 64, 2, 2, EPI_RESID, 1);
+        LAPS_TILE_CASE(1, 128, 64, 2, 2, EPI_RESID, 2);
+        LAPS_TILE_CASE(2, 256, 256, 2, 2, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(2, 256, 256, 2, 2, EPI_RESID, 1);
+        LAPS_TILE_CASE(2, 256, 256, 2, 2, EPI_SWIGLU, 1);
+        LAPS_TILE_CASE(3, 256, 224, 4, 1, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(3, 256, 224, 4, 1, EPI_RESID, 1);
+        LAPS_TILE_CASE(4, 256, 160, 4, 1, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(4, 256, 160, 4, 1, EPI_RESID, 1);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_PARTIAL, 1);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_PARTIAL, 2);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_RESID, 1);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_RESID, 2);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_SWIGLU, 1);
+        LAPS_TILE_CASE(5, 128, 256, 2, 4, EPI_SWIGLU, 2);
         default: break;
     }
+#undef LAPS_TILE_CASE
     laps_set_error("gemm: no kernel for tile %d with epilogue %d", p.cfg, p.epi);
     return LAPS_EINVAL;
 }

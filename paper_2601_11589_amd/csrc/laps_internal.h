@@ -52,6 +52,7 @@ struct GemmPlan {
     int split;        // K slices
     int k_per_split;  // multiple of 64
     int epi;          // epilogue the launch will apply: the requested one if split == 1, else EPI_PARTIAL
+    int ws;           // weight slabs kept in flight per workgroup (register sets): 1 or 2
 };
 GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi);
 size_t laps_gemm_partial_bytes(int m, int n, int k);
