@@ -51,13 +51,13 @@ def attn_flops(cfg, new_len, prefix_len):
     return tot
 
 
-def build_model(cfg, seed):
+def build_model(cfg, seed, n_layers=None):
     from paper_2601_11589_amd import api, inputs
     ctx = api.LapsCtx(cfg, max_positions=8192 + 64)
     layers = []
     host_layers = []
     t0 = time.perf_counter()
-    for l in range(cfg.n_layers):
+    for l in range(n_layers or cfg.n_layers):
         w = inputs.make_layer_weights(cfg, seed, l, threads=min(16, os.cpu_count() or 8))
         layers.append(ctx.upload_layer(w))
         host_layers.append(w)
@@ -236,6 +236,48 @@ def run_long(ctx, layers, cfg, steps, warmup):
     return res
 
 
+# ------------------------------------------------------------------------------------- mixed dual-queue step loop
+def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
+    """configs[4]: 4 long + 512 short / re-prefill requests on an 8-layer stack, Poisson arrivals replayed on a
+    virtual clock that advances by measured GPU step time.  Unified FCFS mixed batches vs temporal disaggregation."""
+    import numpy as np
+    import torch
+    from paper_2601_11589_amd import dualqueue, inputs
+
+    seed = inputs.SEED_BASE + 5
+    b = inputs.make_batch(5)
+    d_x = torch.from_numpy(inputs.make_activations(cfg8, seed, b.n_tokens)).cuda()
+    k_pools, v_pools = ctx8.new_pools(b.n_pages, cfg8.n_layers)
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    for p in k_pools + v_pools:      # cached prefix content: seeded N(0,1) bf16 drawn on the device (26 GB)
+        p.copy_(torch.randn(p.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
+    is_long = b.new_len > 64
+    dq = dualqueue.DualQueue(ctx8, layers8, b.new_len, b.prefix_len, b.page_table, d_x, k_pools, v_pools,
+                             dualqueue.DQParams())
+    zeros = np.zeros(b.n)
+    dq.run_disaggregated(zeros, 0.0)          # warm-up: captures every bucket shape the workload needs
+    dq.run_unified(zeros)
+    u0 = dq.run_unified(zeros)
+    d0 = dq.run_disaggregated(zeros, 0.0)
+    res = {"requests": int(b.n), "real_tokens": int(b.n_tokens), "layers": cfg8.n_layers,
+           "back_to_back": {"unified": u0.summary(b.new_len, is_long), "disaggregated": d0.summary(b.new_len, is_long)},
+           "load": load, "poisson": []}
+    rate = load * b.n / (u0.makespan_us * 1e-6)
+    arr = inputs.poisson_arrivals_us(seed, b.n, rate).astype(np.float64)
+    # long requests are spread uniformly over the arrival horizon
+    horizon = float(arr.max())
+    longs = np.nonzero(is_long)[0]
+    for j, i in enumerate(longs):
+        arr[i] = horizon * j / len(longs)
+    res["arrival_rate_per_s"] = rate
+    res["poisson"].append(dq.run_unified(arr).summary(b.new_len, is_long))
+    for w in windows_us:
+        res["poisson"].append(dq.run_disaggregated(arr, float(w)).summary(b.new_len, is_long))
+    dq.close()
+    del k_pools, v_pools
+    return res
+
+
 # ------------------------------------------------------------------------------------- oracle on host cores
 def cpu_baseline(cfg, host_layers, n_sample_req=24, n_layers=None):
     """fp64 oracle, as it stands, on the first requests of the short workload; all host cores BLAS uses."""
@@ -277,6 +319,8 @@ def main():
     ap.add_argument("--no-long", action="store_true", help="skip the long-prefill workload")
     ap.add_argument("--no-token-max", action="store_true", help="skip the token-max variant of the short workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-dual-queue", action="store_true", help="skip the mixed dual-queue workload (configs[4])")
+    ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
     ap.add_argument("--long-steps", type=int, default=2)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -294,7 +338,9 @@ def main():
     log(f"[bench] device {props.name}, {props.multi_processor_count} CUs, {props.total_memory / 2**30:.0f} GiB; "
         f"peaks used: HBM {HBM_PEAK_GBS} GB/s, bf16 MFMA {MFMA_BF16_PEAK_TFS} TFLOP/s")
     cfg = inputs.qwen32b_cfg(4)
-    ctx, layers, host_layers = build_model(cfg, inputs.SEED_BASE + 2)
+    n_build = 4 if args.no_dual_queue else 8
+    ctx, layers_all, host_layers = build_model(cfg, inputs.SEED_BASE + 2, n_build)
+    layers = layers_all[:4]
 
     short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short")
     g = short.pop("gemm")
@@ -328,8 +374,13 @@ def main():
         line["short_token_max"] = tm
     if not args.no_long:
         line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
+    if not args.no_dual_queue:
+        cfg8 = inputs.qwen32b_cfg(8)
+        ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)
+        line["dual_queue"] = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")])
+        ctx8.close()
     if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(cfg, host_layers)
+        line["cpu_baseline"] = cpu_baseline(cfg, host_layers[:4], n_sample_req=64)
     else:
         line["cpu_baseline"] = None
     print(json.dumps(line), flush=True)

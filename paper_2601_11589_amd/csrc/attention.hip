@@ -293,18 +293,32 @@ int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t
 
 }  // namespace
 
+// Query-row blocking for a batch: rows per workgroup (128 or 256) and an upper bound on the number
+// of (sequence, row block) work items.  Depends only on shapes known to the host.
+static void attn_blocking(int n_seq, int n_tokens, int group, int* mt, int* max_items) {
+    const long total_rows = (long)n_tokens * group;
+    *mt = (total_rows > 128L * n_seq) ? 2 : 1;  // average rows per sequence above one 128-row block
+    const int rows_per_wg = 128 * *mt;
+    // every sequence contributes ceil(rows/rows_per_wg) blocks: at most rows/rows_per_wg + 1
+    *max_items = (int)(total_rows / rows_per_wg) + n_seq;
+}
+
+// Work-item table for laps_launch_attention; depends on the batch only, so a layer stack builds it once.
+int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv,
+                           hipStream_t s) {
+    int mt, max_items;
+    attn_blocking(n_seq, n_tokens, n_q / n_kv, &mt, &max_items);
+    hipLaunchKernelGGL(attn_sched_kernel, dim3(1), dim3(256), 0, s, new_len, n_seq, n_q / n_kv, 128 * mt, tile_start);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
-                          int max_pages, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv, int hd,
+                          int max_pages, int n_seq, int n_tokens, const int* tile_start, int n_q, int n_kv, int hd,
                           hipStream_t s) {
-    const int group = n_q / n_kv;
-    const long total_rows = (long)n_tokens * group;
-    const int mt = (total_rows > 128L * n_seq) ? 2 : 1;  // average rows per sequence above one 128-row block
-    const int rows_per_wg = 128 * mt;
-    // every sequence contributes ceil(rows/rows_per_wg) blocks: at most rows/rows_per_wg + 1
-    const int max_items = (int)(total_rows / rows_per_wg) + n_seq;
-    hipLaunchKernelGGL(attn_sched_kernel, dim3(1), dim3(256), 0, s, new_len, n_seq, group, rows_per_wg, tile_start);
-    LAPS_LAUNCH_CHECK();
+    int mt, max_items;
+    attn_blocking(n_seq, n_tokens, n_q / n_kv, &mt, &max_items);
     if (hd == 128) {
         if (mt == 2) return launch_attn<128, 2>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
         return launch_attn<128, 1>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);

@@ -245,6 +245,10 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
                                   tok_pos, tok_slot, s));
     }
     {
+        ProfScope ps(c, s, LAPS_K_PREP, capturing);
+        LAPS_TRY(laps_launch_attn_sched(new_len, b.n_seq, M, tile_start, cf.n_q_heads, cf.n_kv_heads, s));
+    }
+    {
         ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
         LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, s));
     }
@@ -468,6 +472,8 @@ extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
     int* new_len = reinterpret_cast<int*>(w8 + L.new_len);
     LAPS_TRY(laps_launch_prep(n_tokens, n_seq, cu, seq_len, prefix_len, pt, max_pages, new_len,
                               reinterpret_cast<int*>(w8 + L.tok_pos), reinterpret_cast<int*>(w8 + L.tok_slot), s));
+    LAPS_TRY(laps_launch_attn_sched(new_len, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),
+                                    c->cfg.n_q_heads, c->cfg.n_kv_heads, s));
     return laps_launch_attention(static_cast<const bf16_t*>(q), static_cast<bf16_t*>(out),
                                  static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), cu, new_len,
                                  prefix_len, pt, max_pages, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),

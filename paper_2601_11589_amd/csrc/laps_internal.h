@@ -79,7 +79,9 @@ int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, co
 int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s);
 
 // ----------------------------------------------------------------------------- attention
+int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv,
+                           hipStream_t s);
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
-                          int max_pages, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv, int hd,
+                          int max_pages, int n_seq, int n_tokens, const int* tile_start, int n_q, int n_kv, int hd,
                           hipStream_t s);

@@ -1,0 +1,224 @@
+"""Single-GPU dual-queue step loop: temporal long/short disaggregation against a unified mixed batch.
+
+Section 3.2 of the paper keeps two queues, Q_s and Q_l, classified by prompt length, and lets an
+instance execute one class at a time; short batches fill captured bucket shapes after a waiting window
+(Section 3.1), long requests advance alone in fixed chunks.  Written for instances, the rule is read
+here for one GPU as: every GPU step is either the planned bucket batches of the waiting short requests
+(each one captured-graph replay) or one chunk of the oldest long request; short requests are dispatched
+when the oldest has waited `window_us` or when `short_token_budget` padded tokens are waiting, otherwise
+the next long chunk runs.  When few tokens wait, the buckets are fused into the largest one needed (the
+paper's "graph fusion", Section 3.1): a replay then costs one pass over the weights whatever its shape.  The baseline is the policy the paper argues against (Section 2.3): one FCFS
+queue, each step a token-budget batch that mixes the next long chunk with whatever short requests fit.
+
+Arrivals are virtual timestamps; the clock advances by the measured GPU time of every step (HIP events
+around the step, host launch overhead included when it stalls the GPU) and jumps over idle gaps.
+Only sequencing lives here: every step runs through the C-ABI binding.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from . import api, runner
+
+
+@dataclass
+class DQParams:
+    short_max_len: int = 64
+    len_buckets: tuple = (16, 32, 64)
+    depths: tuple = (1, 2, 4, 8, 16, 32, 64)
+    short_token_budget: int = 2048     # padded tokens per captured short graph (token-max rule M_s)
+    long_chunk: int = 2048             # C_l
+    unified_budget: int = 2048         # tokens per step of the unified baseline
+    window_us: float = 1000.0          # fixed waiting window W
+    merge_below: int = 512             # graph fusion: below this many waiting padded tokens (where a replay
+                                       # costs one pass over the weights whatever its shape) all waiting short
+                                       # requests share the largest needed length bucket: one replay, not three
+
+
+@dataclass
+class DQResult:
+    mode: str
+    makespan_us: float
+    gpu_busy_us: float
+    n_steps: int
+    finish_us: np.ndarray
+    latency_us: np.ndarray
+    step_kinds: dict = field(default_factory=dict)
+
+    def summary(self, new_len, is_long) -> dict:
+        lat_s, lat_l = self.latency_us[~is_long], self.latency_us[is_long]
+        pc = lambda v, q: float(np.percentile(v, q)) / 1e3 if len(v) else None
+        return {"mode": self.mode, "makespan_ms": self.makespan_us / 1e3, "gpu_busy_ms": self.gpu_busy_us / 1e3,
+                "steps": self.n_steps, "step_kinds": self.step_kinds,
+                "tokens_per_s": float(np.sum(new_len)) / (self.makespan_us * 1e-6),
+                "short_latency_ms": {"p50": pc(lat_s, 50), "p90": pc(lat_s, 90), "mean": float(lat_s.mean()) / 1e3},
+                "long_latency_ms": {"p50": pc(lat_l, 50), "p90": pc(lat_l, 90), "mean": float(lat_l.mean()) / 1e3}}
+
+
+class DualQueue:
+    """Holds the device-resident workload (packed activations, page tables, pools) and runs either policy."""
+
+    def __init__(self, ctx: api.LapsCtx, layers, new_len, prefix_len, page_table, d_x: torch.Tensor, k_pools, v_pools,
+                 params: DQParams, keep_outputs: bool = False):
+        self.ctx, self.layers, self.p = ctx, layers, params
+        self.new_len = np.asarray(new_len, np.int64)
+        self.prefix_len = np.asarray(prefix_len, np.int64)
+        self.page_table = np.ascontiguousarray(page_table, np.int32)
+        self.d_page_table = torch.from_numpy(self.page_table).cuda()
+        self.cu = np.concatenate([[0], np.cumsum(self.new_len)])
+        self.d_x, self.k_pools, self.v_pools = d_x, k_pools, v_pools
+        self.n = len(self.new_len)
+        self.is_long = self.new_len > params.short_max_len
+        self.stream = torch.cuda.Stream()
+        self.short = runner.ShortRunner(ctx, layers, k_pools, v_pools, self.page_table.shape[1], self.stream)
+        self.out = torch.zeros_like(d_x) if keep_outputs else None
+        ctx.workspace(max(params.unified_budget, params.long_chunk), min(self.n, params.unified_budget))
+        self._ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+
+    # ------------------------------------------------------------------ timed execution of one step
+    def _timed(self, fn) -> float:
+        e0, e1 = self._ev
+        e0.record(self.stream)
+        fn()
+        e1.record(self.stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3   # microseconds
+
+    def _run_varlen(self, segs) -> float:
+        """segs: list of (request, first new token, count).  One un-captured packed batch."""
+        with torch.cuda.stream(self.stream):
+            ids = [s[0] for s in segs]
+            x = torch.cat([self.d_x[self.cu[r] + a: self.cu[r] + a + c] for r, a, c in segs])
+            cu = torch.tensor(np.concatenate([[0], np.cumsum([c for _, _, c in segs])]), dtype=torch.int32, device="cuda")
+            pre = torch.tensor([int(self.prefix_len[r]) + a for r, a, _ in segs], dtype=torch.int32, device="cuda")
+            pt = self.d_page_table[torch.tensor(ids, device="cuda")].contiguous()
+            out = torch.empty_like(x)
+            self.stream.synchronize()          # input placement is not part of the step
+            us = self._timed(lambda: self.ctx.laps_prefill_stack(self.layers, cu, None, pre, pt, self.k_pools,
+                                                                 self.v_pools, x, out, self.stream))
+            if self.out is not None:
+                o = 0
+                for r, a, c in segs:
+                    self.out[self.cu[r] + a: self.cu[r] + a + c] = out[o:o + c]
+                    o += c
+                self.stream.synchronize()
+        return us
+
+    def _run_short_batches(self, req_ids):
+        """Plans the waiting short requests and replays one captured graph per planned batch.
+        Returns a list of (request ids, microseconds) per batch."""
+        p = self.p
+        ids = list(req_ids)
+        buckets = list(p.len_buckets)
+        need = [next(lb for lb in buckets if lb >= self.new_len[r]) for r in ids]
+        if sum(need) < p.merge_below:
+            buckets = [max(need)]
+        plan = api.laps_plan_buckets(p.short_max_len, buckets, list(p.depths), p.short_token_budget,
+                                     p.long_chunk, self.new_len[ids], self.prefix_len[ids])
+        assert not plan["longs"]
+        cu_local = np.concatenate([[0], np.cumsum(self.new_len[ids])])
+        with torch.cuda.stream(self.stream):
+            x_local = torch.cat([self.d_x[self.cu[r]: self.cu[r + 1]] for r in ids])
+            staged = runner.stage_short_batches(plan, self.new_len[ids], self.prefix_len[ids], self.page_table[ids],
+                                                cu_local, x_local, self.d_x.shape[1])
+            self.stream.synchronize()
+        res = []
+        for sb in staged:
+            out = None
+            if self.out is not None:
+                out = torch.empty((sb.n_real * sb.len_bucket, self.d_x.shape[1]), dtype=torch.float32, device="cuda")
+            self.short.graph_for(sb.len_bucket, sb.depth)      # capture (first use) is not part of the step
+            us = self._timed(lambda: self.short.run(sb, out))
+            if out is not None:
+                for slot, j in enumerate(sb.req_ids):
+                    r = ids[j]
+                    self.out[self.cu[r]: self.cu[r + 1]] = out[slot * sb.len_bucket: slot * sb.len_bucket + int(self.new_len[r])]
+                self.stream.synchronize()
+            res.append(([ids[j] for j in sb.req_ids], us))
+        return res
+
+    # ------------------------------------------------------------------ policies
+    def run_unified(self, arrival_us) -> DQResult:
+        arrival = np.asarray(arrival_us, np.float64)
+        order = list(np.argsort(arrival, kind="stable"))
+        done = np.zeros(self.n, np.int64)
+        finish = np.zeros(self.n)
+        t, busy, steps, nxt = 0.0, 0.0, 0, 0
+        queue = []
+        while nxt < self.n or queue:
+            while nxt < self.n and arrival[order[nxt]] <= t:
+                queue.append(order[nxt])
+                nxt += 1
+            if not queue:
+                t = arrival[order[nxt]]
+                continue
+            budget, segs = self.p.unified_budget, []
+            for r in queue:                                   # FCFS, the head long request is chunked by what is left
+                if budget == 0:
+                    break
+                c = int(min(self.new_len[r] - done[r], budget))
+                segs.append((r, int(done[r]), c))
+                budget -= c
+            us = self._run_varlen(segs)
+            t += us
+            busy += us
+            steps += 1
+            for r, a, c in segs:
+                done[r] += c
+                if done[r] == self.new_len[r]:
+                    finish[r] = t
+            queue = [r for r in queue if done[r] < self.new_len[r]]
+        return DQResult("unified", t, busy, steps, finish, finish - arrival, {"mixed": steps})
+
+    def run_disaggregated(self, arrival_us, window_us=None) -> DQResult:
+        p = self.p
+        window = p.window_us if window_us is None else window_us
+        arrival = np.asarray(arrival_us, np.float64)
+        order = list(np.argsort(arrival, kind="stable"))
+        done = np.zeros(self.n, np.int64)
+        finish = np.zeros(self.n)
+        t, busy, nxt = 0.0, 0.0, 0
+        kinds = {"short_graph": 0, "long_chunk": 0}
+        q_s, q_l = [], []
+        bucket_of = lambda r: next(lb for lb in p.len_buckets if lb >= self.new_len[r])
+        while nxt < self.n or q_s or q_l:
+            while nxt < self.n and arrival[order[nxt]] <= t:
+                r = order[nxt]
+                (q_l if self.is_long[r] else q_s).append(r)
+                nxt += 1
+            waiting_tokens = sum(bucket_of(r) for r in q_s)
+            due = q_s and (t - arrival[q_s[0]] >= window or waiting_tokens >= p.short_token_budget
+                           or (not q_l and nxt >= self.n))
+            if due:
+                batch, q_s = q_s, []
+                for ids, us in self._run_short_batches(batch):
+                    t += us
+                    busy += us
+                    kinds["short_graph"] += 1
+                    for r in ids:
+                        done[r] = self.new_len[r]
+                        finish[r] = t
+            elif q_l:
+                r = q_l[0]
+                c = int(min(self.new_len[r] - done[r], p.long_chunk))
+                us = self._run_varlen([(r, int(done[r]), c)])
+                t += us
+                busy += us
+                kinds["long_chunk"] += 1
+                done[r] += c
+                if done[r] == self.new_len[r]:
+                    finish[r] = t
+                    q_l.pop(0)
+            else:
+                wake = [arrival[order[nxt]]] if nxt < self.n else []
+                if q_s:
+                    wake.append(arrival[q_s[0]] + window)
+                t = max(t, min(wake))
+        return DQResult(f"disaggregated(W={window:g}us)", t, busy, kinds["short_graph"] + kinds["long_chunk"], finish,
+                        finish - arrival, kinds)
+
+    def close(self):
+        self.short.close()
