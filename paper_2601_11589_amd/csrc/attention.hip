@@ -20,7 +20,6 @@
 namespace {
 
 constexpr int KT = 64;      // keys per tile (4 pages)
-constexpr int NTHR = 256;   // 4 waves
 
 __device__ __forceinline__ int swz8(int row, int c) { return c ^ ((row & 7) ^ ((row >> 3) & 1)); }
 __device__ __forceinline__ int swz16(int row, int c) { return c ^ (row & 15); }
@@ -52,22 +51,29 @@ __global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__
     if (threadIdx.x == 0) tile_start[n_seq] = carry;
 }
 
-template <int HD, int MT>
-__global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out,
-                                                     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool,
-                                                     const int* __restrict__ row_start, const int* __restrict__ new_len,
-                                                     const int* __restrict__ prefix_len, const int* __restrict__ page_table,
-                                                     int max_pages, const int* __restrict__ tile_start, int n_seq,
-                                                     int n_q, int n_kv, float scale_log2e) {
+// NW waves per workgroup, one 32-row query tile per wave: rows per workgroup = 32 * NW.  With NW = 8
+// two waves share a SIMD, so one wave's softmax (VALU, exp) overlaps the other's MFMAs.
+template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out,
+                                                        const bf16_t* __restrict__ k_pool,
+                                                        const bf16_t* __restrict__ v_pool,
+                                                        const int* __restrict__ row_start,
+                                                        const int* __restrict__ new_len,
+                                                        const int* __restrict__ prefix_len,
+                                                        const int* __restrict__ page_table, int max_pages,
+                                                        const int* __restrict__ tile_start, int n_seq, int n_q,
+                                                        int n_kv, float scale_log2e) {
+    constexpr int NTHR = NW * 64;
     constexpr int CPR = HD / 8;            // 16-byte chunks per K row
     constexpr int CPP = HD * 2;            // 16-byte chunks per page (K and V alike)
     constexpr int NLD = KT * CPR / NTHR;   // chunk loads per thread per tile, K and V each
     constexpr int KSTEPS = HD / 16;        // MFMA k-steps over head_dim
     constexpr int NI = HD / 32;            // output sub-tiles over head_dim
-    constexpr int ROWS = 128 * MT;
+    constexpr int ROWS = 32 * NW;
+    static_assert(KT * CPR % NTHR == 0, "tile chunks must divide over the threads");
 
-    __shared__ __align__(16) u32x4 Ks[KT * CPR];
-    __shared__ __align__(16) u32x4 Vs[HD * 8];
+    __shared__ __align__(16) u32x4 Ks[2][KT * CPR];   // double buffered: one barrier per tile
+    __shared__ __align__(16) u32x4 Vs[2][HD * 8];
 
     const int item = blockIdx.x;
     if (item >= tile_start[n_seq]) return;
@@ -95,38 +101,26 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 31, lh = lane >> 5;
 
-    // ---- Q fragments (registers for the whole kernel) and per-row causal limits
-    bf16x8 qf[MT][KSTEPS];
-    int limit[MT];      // last visible key of this lane's row
-    int row_id[MT];     // unclamped row index
-    int vis_max = 0;    // wave-uniform: last key any row of this wave sees
+    // ---- this wave's 32 query rows: Q fragments stay in registers for the whole kernel
+    const int base = R0 + wave * 32;
+    const int row_id = base + lm;
+    const int rc = row_id < n_rows ? row_id : n_rows - 1;
+    const int tq = rc / G, gq = rc - tq * G;
+    const int limit = H + tq;                                        // last visible key of this lane's row
+    const int vis_min = H + (base < n_rows ? base : n_rows - 1) / G;  // wave-uniform: every row sees keys <= vis_min
+    const int vis_max = (base < n_rows) ? H + (base + 31 < n_rows ? base + 31 : n_rows - 1) / G : -1;
+    bf16x8 qf[KSTEPS];
+    {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(q + (tok0 + tq) * q_stride + (size_t)(kvh * G + gq) * HD);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int base = R0 + (mt * 4 + wave) * 32;
-        const int r = base + lm;
-        row_id[mt] = r;
-        const int rc = r < n_rows ? r : n_rows - 1;
-        const int t = rc / G, g = rc - t * G;
-        limit[mt] = H + t;
-        const int last = (base + 31 < n_rows ? base + 31 : n_rows - 1);
-        const int vm = (base < n_rows) ? H + last / G : -1;
-        vis_max = vm > vis_max ? vm : vis_max;
-        const u32x4* qp = reinterpret_cast<const u32x4*>(q + (tok0 + t) * q_stride + (size_t)(kvh * G + g) * HD);
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) qf[mt][kk] = __builtin_bit_cast(bf16x8, qp[kk * 2 + lh]);
+        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, qp[kk * 2 + lh]);
     }
-
-    f32x16 o[MT][NI];
-    float m_run[MT], l_run[MT];
+    f32x16 o[NI];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        m_run[mt] = -INFINITY;
-        l_run[mt] = 0.f;
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[mt][ni][i] = 0.f;
-    }
+        for (int i = 0; i < 16; ++i) o[ni][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;   // running max (in log2 units, already scaled) and partial row sum
 
     // ---- tile copy assignment: chunk c = tid + i*NTHR of the tile's 4 pages
     u32x4 kreg[NLD], vreg[NLD];
@@ -144,7 +138,7 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
             vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];
         }
     };
-    auto store_tile = [&](int j0) {
+    auto store_tile = [&](int j0, int buf) {
         const bool tail = (j0 + KT > kv_len);
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -152,7 +146,7 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
             const int pi = c / CPP, within = c % CPP;
             {   // K page is [16 keys][HD]
                 const int key = pi * LAPS_PAGE + within / CPR, kc = within % CPR;
-                Ks[key * CPR + (CPR == 16 ? swz16(key, kc) : swz8(key, kc))] = kreg[i];
+                Ks[buf][key * CPR + (CPR == 16 ? swz16(key, kc) : swz8(key, kc))] = kreg[i];
             }
             {   // V page is [HD][16 keys]: chunk = 8 consecutive keys of one head_dim index
                 const int e = within / 2, half = within & 1;
@@ -167,62 +161,63 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
                         v[w] = x;
                     }
                 }
-                Vs[e * 8 + swz8(e, pi * 2 + half)] = v;
+                Vs[buf][e * 8 + swz8(e, pi * 2 + half)] = v;
             }
         }
     };
 
-    load_tile(0);
-    for (int j0 = 0; j0 < kv_end; j0 += KT) {
-        __syncthreads();
-        store_tile(j0);
-        __syncthreads();
-        if (j0 + KT < kv_end) load_tile(j0 + KT);
-        if (j0 > vis_max) continue;  // wave-uniform: nothing of this tile is visible to this wave
+    // MFMA row rho = lm of the first product holds key 16(a/2) + 8h + 4(a%2) + b with rho = 8a + 4h + b
+    const int ra = lm >> 3, rh = (lm >> 2) & 1, rb = lm & 3;
+    const int krow = 16 * (ra >> 1) + 8 * rh + 4 * (ra & 1) + rb;
 
-        // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key sub-tiles)
-        f32x16 s[MT][2];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+    load_tile(0);
+    store_tile(0, 0);
+    if (KT < kv_end) load_tile(KT);
+    __syncthreads();
+    int buf = 0;
+    for (int j0 = 0; j0 < kv_end; j0 += KT, buf ^= 1) {
+        // stage the next tile (already in registers) into the other buffer, refill the registers
+        if (j0 + KT < kv_end) {
+            store_tile(j0 + KT, buf ^ 1);
+            if (j0 + 2 * KT < kv_end) load_tile(j0 + 2 * KT);
+        }
+        if (j0 <= vis_max) {  // wave-uniform: something of this tile is visible to this wave
+            // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key sub-tiles)
+            f32x16 s[2];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[mt][sub][i] = 0.f;
-        // MFMA row rho = lm holds key 16(a/2) + 8h + 4(a%2) + b with rho = 8a + 4h + b
-        const int ra = lm >> 3, rh = (lm >> 2) & 1, rb = lm & 3;
-        const int krow = 16 * (ra >> 1) + 8 * rh + 4 * (ra & 1) + rb;
+                for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
+            for (int kk = 0; kk < KSTEPS; ++kk) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const int row = sub * 32 + krow;
-                const int ch = kk * 2 + lh;
-                const bf16x8 kf = __builtin_bit_cast(bf16x8, Ks[row * CPR + (CPR == 16 ? swz16(row, ch) : swz8(row, ch))]);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    s[mt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mt][kk], s[mt][sub], 0, 0, 0);
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int row = sub * 32 + krow;
+                    const int ch = kk * 2 + lh;
+                    const bf16x8 kf = __builtin_bit_cast(
+                        bf16x8, Ks[buf][row * CPR + (CPR == 16 ? swz16(row, ch) : swz8(row, ch))]);
+                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
+                }
             }
-        }
-
-        // ---- causal mask + online softmax, one query row per lane (shared with lane ^ 32)
-        bf16x8 pf[MT][2][2];
+            // ---- causal mask (diagonal tiles only) + online softmax, one query row per lane (shared with lane^32)
+            if (j0 + KT - 1 > vis_min) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int a = i >> 2, b = i & 3;
+                        const int key = j0 + sub * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
+                        s[sub][i] = (key <= limit) ? s[sub][i] : -INFINITY;
+                    }
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int a = i >> 2, b = i & 3;
-                    const int key = j0 + sub * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
-                    const float v = (key <= limit[mt]) ? s[mt][sub][i] * scale_log2e : -INFINITY;
-                    s[mt][sub][i] = v;
-                    mx = fmaxf(mx, v);
-                }
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[sub][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[mt], mx);           // finite from the first tile on (key 0 is visible)
-            const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_new);
-            m_run[mt] = m_new;
+            const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite from the first tile on (key 0 is visible)
+            bf16x8 pf[2][2];
             float psum = 0.f;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
@@ -231,62 +226,61 @@ __global__ __launch_bounds__(NTHR) void attn_kernel(const bf16_t* __restrict__ q
                     bf16x8 pk;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(s[mt][sub][8 * u + e] - m_new);
+                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + e], scale_log2e, -m_new));
                         psum += p;
                         pk[e] = (__bf16)p;
                     }
-                    pf[mt][sub][u] = pk;
+                    pf[sub][u] = pk;
                 }
-            l_run[mt] = l_run[mt] * alpha + psum;
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= alpha;
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[mt][ni][i] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T
+                    for (int i = 0; i < 16; ++i) o[ni][i] *= alpha;
+                m_run = m_new;
+            }
+            l_run += psum;
+            // ---- O^T += V^T P^T
 #pragma unroll
-        for (int u2 = 0; u2 < 4; ++u2) {
+            for (int u2 = 0; u2 < 4; ++u2) {
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int row = ni * 32 + lm;
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, Vs[row * 8 + swz8(row, u2 * 2 + lh)]);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    o[mt][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mt][u2 >> 1][u2 & 1], o[mt][ni], 0, 0, 0);
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int row = ni * 32 + lm;
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, Vs[buf][row * 8 + swz8(row, u2 * 2 + lh)]);
+                    o[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u2 >> 1][u2 & 1], o[ni], 0, 0, 0);
+                }
             }
         }
+        __syncthreads();
     }
 
     // ---- normalise and store: lane owns row r; register i of sub-tile ni is head_dim index
     //      ni*32 + 8*(i/4) + 4*(lane/32) + i%4
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const float l_tot = l_run[mt] + __shfl_xor(l_run[mt], 32, 64);
-        const int r = row_id[mt];
-        if (r >= n_rows) continue;
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (row_id < n_rows) {
         const float inv = 1.f / l_tot;
-        const int t = r / G, g = r - t * G;
-        bf16_t* op = out + (tok0 + t) * q_stride + (size_t)(kvh * G + g) * HD;
+        bf16_t* op = out + (tok0 + tq) * q_stride + (size_t)(kvh * G + gq) * HD;
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 u32x2 w;
-                w.x = pack_bf16x2(o[mt][ni][4 * a] * inv, o[mt][ni][4 * a + 1] * inv);
-                w.y = pack_bf16x2(o[mt][ni][4 * a + 2] * inv, o[mt][ni][4 * a + 3] * inv);
+                w.x = pack_bf16x2(o[ni][4 * a] * inv, o[ni][4 * a + 1] * inv);
+                w.y = pack_bf16x2(o[ni][4 * a + 2] * inv, o[ni][4 * a + 3] * inv);
                 *reinterpret_cast<u32x2*>(op + ni * 32 + 8 * a + 4 * lh) = w;
             }
     }
 }
 
-template <int HD, int MT>
+template <int HD, int NW>
 int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool, const int* row_start,
                 const int* new_len, const int* prefix_len, const int* page_table, int max_pages, const int* tile_start,
                 int n_seq, int max_items, int n_q, int n_kv, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
-    hipLaunchKernelGGL((attn_kernel<HD, MT>), dim3(max_items, n_kv), dim3(NTHR), 0, s, q, out, k_pool, v_pool, row_start,
-                       new_len, prefix_len, page_table, max_pages, tile_start, n_seq, n_q, n_kv, scale_log2e);
+    hipLaunchKernelGGL((attn_kernel<HD, NW>), dim3(max_items, n_kv), dim3(NW * 64), 0, s, q, out, k_pool, v_pool,
+                       row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, n_q, n_kv, scale_log2e);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -320,12 +314,12 @@ int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, co
     int mt, max_items;
     attn_blocking(n_seq, n_tokens, n_q / n_kv, &mt, &max_items);
     if (hd == 128) {
-        if (mt == 2) return launch_attn<128, 2>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<128, 1>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
     }
     if (hd == 64) {
-        if (mt == 2) return launch_attn<64, 2>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<64, 1>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
     }
     laps_set_error("attention: head_dim %d not supported (64 or 128)", hd);
     return LAPS_EINVAL;

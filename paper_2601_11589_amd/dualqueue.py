@@ -116,7 +116,7 @@ class DualQueue:
         need = [next(lb for lb in buckets if lb >= self.new_len[r]) for r in ids]
         if sum(need) < p.merge_below:
             buckets = [max(need)]
-        plan = api.laps_plan_buckets(p.short_max_len, buckets, list(p.depths), p.short_token_budget,
+        plan = api.laps_plan_buckets(min(p.short_max_len, buckets[-1]), buckets, list(p.depths), p.short_token_budget,
                                      p.long_chunk, self.new_len[ids], self.prefix_len[ids])
         assert not plan["longs"]
         cu_local = np.concatenate([[0], np.cumsum(self.new_len[ids])])
