@@ -322,6 +322,9 @@ def main():
     ap.add_argument("--no-dual-queue", action="store_true", help="skip the mixed dual-queue workload (configs[4])")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
     ap.add_argument("--long-steps", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (known size) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings of the same run can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (replicas are independent; see DESIGN.md); "
@@ -337,6 +340,14 @@ def main():
     props = torch.cuda.get_device_properties(0)
     log(f"[bench] device {props.name}, {props.multi_processor_count} CUs, {props.total_memory / 2**30:.0f} GiB; "
         f"peaks used: HBM {HBM_PEAK_GBS} GB/s, bf16 MFMA {MFMA_BF16_PEAK_TFS} TFLOP/s")
+    if args.calibrate_copy:
+        src = torch.ones(256 * 2**20 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] calibration: 5 plain device copies of 268435456 bytes (read) + 268435456 bytes (write) each")
+        del src, dst
     cfg = inputs.qwen32b_cfg(4)
     n_build = 4 if args.no_dual_queue else 8
     ctx, layers_all, host_layers = build_model(cfg, inputs.SEED_BASE + 2, n_build)
@@ -344,13 +355,9 @@ def main():
 
     short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short")
     g = short.pop("gemm")
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("short_gemm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
+    # plain copy of known size (profiles/short_bucket_gemm_hbm_traffic.md); valid for the default token budget
+    traffic = 286.1e6 if args.token_budget == 128 else None
     line = {
         "metric": METRIC, "value": short["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": short["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -360,7 +367,7 @@ def main():
                    "layers": cfg.n_layers, "requests": 256, "token_budget": args.token_budget},
         "latency_ms": {"p50": short["latency_ms_p50"], "p90": short["latency_ms_p90"],
                        "what": "per request: stage+replay time of the bucket batch that serves it"},
-        "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<128,128,2,2> (all four projections)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<128,256,2,4,*,2> (all four projections of every layer)",
                      "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g["GBps"] / HBM_PEAK_GBS,
                      "traffic": traffic, "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"],
                      "launches": g["launches"], "TFLOPs": g["TFLOPs"]},
