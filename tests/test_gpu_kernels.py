@@ -297,3 +297,52 @@ def test_prefill_argument_errors(tiny_ctx):
     assert rc == -1
     with pytest.raises(api.LapsError):
         api.LapsCtx(inputs.ModelCfg(250, 4, 2, 64, 512, 1), 16)        # hidden not a multiple of 128
+
+
+def test_many_single_token_sequences_and_scan_over_256():
+    """300 sequences of 1-3 tokens: the query-block table is built by a scan that loops over 256-entry
+    chunks; length-1 rows without prefix must return v of their kv head through the whole layer."""
+    cfg = inputs.tiny_cfg(1)
+    rng = np.random.default_rng(17)
+    new_len = rng.integers(1, 4, 300)
+    prefix = np.where(rng.random(300) < 0.5, 0, rng.integers(1, 40, 300))
+    case = Case(cfg, new_len, prefix, 4711)
+    ctx = api.LapsCtx(cfg, max_positions=128)
+    case.to_device(ctx)
+    y_gpu = case.run_stack()
+    check_stack(case, y_gpu, "300 tiny sequences")
+    ctx.close()
+
+
+def test_stack_is_deterministic_bit_for_bit():
+    """Split-K sums are reduced in slice order and nothing uses atomics: two runs on fresh caches agree bitwise."""
+    cfg = inputs.tiny_cfg(2)
+    ctx = api.LapsCtx(cfg, max_positions=512)
+    a = Case(cfg, [64, 3, 128, 17], [5, 100, 0, 31], 2024).to_device(ctx)
+    ya = a.run_stack()
+    b = Case(cfg, [64, 3, 128, 17], [5, 100, 0, 31], 2024).to_device(ctx)
+    yb = b.run_stack()
+    assert np.array_equal(ya, yb)
+    ka, va = a.gathered_new_kv(1)
+    kb, vb = b.gathered_new_kv(1)
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    ctx.close()
+
+
+def test_graph_stage_rejects_too_many_slots_and_empty_replay_is_harmless():
+    cfg = inputs.tiny_cfg(1)
+    ctx = api.LapsCtx(cfg, max_positions=64)
+    case = Case(cfg, [4, 4], [0, 0], 9).to_device(ctx)
+    stream = torch.cuda.Stream()
+    g = ctx.laps_graph_capture(case.dev_layers, 16, 2, case.page_table.shape[1], case.k_pools, case.v_pools, stream)
+    three = torch.zeros(3, dtype=torch.int32, device="cuda")
+    tab = torch.zeros((3, case.page_table.shape[1]), dtype=torch.int32, device="cuda")
+    with pytest.raises(api.LapsError):
+        g.laps_graph_stage(3, three, three, tab, None, stream)
+    g.laps_graph_stage(0, None, None, None, None, stream)      # all slots empty
+    g.laps_graph_replay(stream)
+    stream.synchronize()
+    kp = case.k_pools[0].view(torch.int16)
+    assert bool((kp == 0x7FC0).all())                           # nothing was appended to the poisoned cache
+    g.close()
+    ctx.close()

@@ -96,3 +96,16 @@ def test_library_exports_every_declared_symbol(repo_root):
     for name in declared:
         assert hasattr(lib, name)
     assert lib.laps_version().decode().startswith("laps-gfx950")
+
+
+def test_planner_under_address_and_ub_sanitizers(repo_root, tmp_path):
+    """Host code only: the planner and a random-input driver built with -fsanitize=address,undefined."""
+    exe = str(tmp_path / "planner_san")
+    src = [os.path.join(repo_root, "paper_2601_11589_amd", "csrc", "planner.cpp"),
+           os.path.join(repo_root, "tests", "planner_sanitize_driver.cpp")]
+    build = subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                            "-o", exe] + src, capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0 and run.stdout.strip().endswith("OK"), (run.stdout[-500:], run.stderr[-2000:])
