@@ -236,6 +236,19 @@ def run_long(ctx, layers, cfg, steps, warmup):
     return res
 
 
+# ------------------------------------------------------------------------------------- latency model fit
+def run_latency_model(layers, cfg):
+    """Run-time fit of the compute / memory latency model (Section 2.1) on single-request passes."""
+    from paper_2601_11589_amd import api, latency_fit
+    new_lens, hist_lens = (16, 32, 64, 128, 256, 512, 1024, 2048), (0, 1024, 4096, 16384)
+    ctx = api.LapsCtx(cfg, max_positions=max(new_lens) + max(hist_lens))
+    samples = latency_fit.collect_samples(ctx, layers, new_lens, hist_lens)
+    res = latency_fit.fit_and_boundaries(samples, cfg, len(layers), report_hist=hist_lens)
+    res["samples"] = [{k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()} for s in samples]
+    ctx.close()
+    return res
+
+
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop
 def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
     """configs[4]: 4 long + 512 short / re-prefill requests on an 8-layer stack, Poisson arrivals replayed on a
@@ -273,6 +286,18 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
     res["poisson"].append(dq.run_unified(arr).summary(b.new_len, is_long))
     for w in windows_us:
         res["poisson"].append(dq.run_disaggregated(arr, float(w)).summary(b.new_len, is_long))
+    # Adaptive-Wait-Depth batching of the short queue (Algorithm 1): deadline-free, then with a 50 ms TTFT deadline
+    s_hat = d0.step_kinds["short_busy_us"] / max(d0.step_kinds["short_graph"], 1)   # mean short step, measured
+    dq.run_awd(zeros)                          # warm-up: captures the fused shapes AWD dispatches
+    res["back_to_back"]["awd"] = dq.run_awd(zeros, s_hat_us=s_hat).summary(b.new_len, is_long)
+    res["poisson"].append(dq.run_awd(arr, s_hat_us=s_hat, w_max_us=10_000.0).summary(b.new_len, is_long))
+    ddl = arr + 50_000.0
+    for sla_window in (False, True):
+        r = dq.run_awd(arr, ddl_us=ddl, s_hat_us=s_hat, sigma_us=2_000.0, w_max_us=10_000.0, t_max_us=25_000.0,
+                       delta_us=1_000.0, sla_window=sla_window)
+        sm = r.summary(b.new_len, is_long)
+        sm["short_deadline_50ms_met_frac"] = float(np.mean(r.latency_us[~is_long] <= 50_000.0))
+        res["poisson"].append(sm)
     dq.close()
     del k_pools, v_pools
     return res
@@ -320,6 +345,7 @@ def main():
     ap.add_argument("--no-token-max", action="store_true", help="skip the token-max variant of the short workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-dual-queue", action="store_true", help="skip the mixed dual-queue workload (configs[4])")
+    ap.add_argument("--no-latency-model", action="store_true", help="skip the run-time latency-model fit")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
     ap.add_argument("--long-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -381,6 +407,8 @@ def main():
         line["short_token_max"] = tm
     if not args.no_long:
         line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
+    if not args.no_latency_model:
+        line["latency_model"] = run_latency_model(layers, cfg)
     if not args.no_dual_queue:
         cfg8 = inputs.qwen32b_cfg(8)
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)

@@ -226,6 +226,67 @@ enum { LAPS_K_PREP = 0, LAPS_K_RMSNORM, LAPS_K_GEMM_QKV, LAPS_K_GEMM_O, LAPS_K_G
 int laps_prof_enable(laps_ctx* ctx, int32_t on);
 int laps_prof_read(laps_ctx* ctx, double* ms_out /*[LAPS_K_COUNT]*/, int64_t* count_out /*[LAPS_K_COUNT]*/);
 
+/* ------------------------------------------------------------------ latency model (host, double)
+ * Section 2.1: T_comp(L,H) = alpha L (L + 2H) + beta L, T_mem(L,H) = gamma_w L + gamma_r H for L new and H
+ * historical tokens.  Boundaries where the two meet: prefill (H = 0) max(0, (gamma_w - beta)/alpha);
+ * re-prefill the positive root of alpha L^2 + (2 alpha H + beta - gamma_w) L - gamma_r H = 0, which tends
+ * to gamma_r / (2 alpha) for large H.  Below the boundary a request is memory-bound ("short").
+ * Both return NaN when alpha <= 0 (or H < 0). */
+double laps_lm_boundary_prefill(double alpha, double beta, double gamma_w);
+double laps_lm_boundary_reprefill(double alpha, double beta, double gamma_w, double gamma_r, double hist_len);
+/* Least-squares fit of (alpha, beta) to t_comp and (gamma_w, gamma_r) to t_mem from n samples (host arrays
+ * [n]; any consistent time unit).  coef_out[4] = {alpha, beta, gamma_w, gamma_r}.  EINVAL if n < 2 or the
+ * samples do not vary L and H independently. */
+int laps_lm_fit(int32_t n, const double* new_len, const double* hist_len, const double* t_comp, const double* t_mem,
+                double* coef_out);
+
+/* ------------------------------------------------------------------ Adaptive-Wait-Depth batching (host)
+ * Algorithm 1 and Section 3.2a.  The object holds the waiting window W, the target depth D and the timer of
+ * the current round; the caller owns the short queue and the clock (any origin, microseconds) and polls at
+ * every event: a short request arrives, the instance becomes free, or the wake-up time of the previous poll.
+ *   W starts as clip(first_slack_us, [w_min, w_max]) with first_slack_us = min_i(DDL_i - t - S_hat) over the
+ *   requests known at creation (INFINITY if none); D starts as the deepest captured shape within mem_budget.
+ *   mem(G) = len_bucket * depth padded tokens.  t_max_us = INFINITY disables the head-of-line cap; a request
+ *   without a deadline has ddl = INFINITY.  sla_window != 0 takes, when a round's timer starts,
+ *   W = clip(min(W_SLA, W_GR)) (Section 3.2a) with rate_hat (requests per microsecond) from the caller.
+ *   d_regrow != 0 adds what the printed algorithm lacks, a way for D to rise again: a round that fills D while
+ *   at least D more requests wait moves D to the next larger captured depth (never above its start value). */
+typedef struct laps_awd laps_awd;
+typedef struct {
+    int32_t n_len_buckets;
+    const int32_t* len_buckets; /* host, strictly ascending */
+    int32_t n_depths;
+    const int32_t* depths;      /* host, strictly ascending */
+    int64_t mem_budget;         /* M, padded tokens; >= depths[0] * largest bucket */
+    double sigma_us;            /* slack trigger */
+    double w_min_us, w_max_us;  /* 0 <= w_min <= w_max < inf */
+    double s_hat_us;            /* service-time estimate of one short step */
+    double t_max_us;            /* head-of-line cap, INFINITY for none */
+    double delta_us;            /* safety margin of W_SLA */
+    double rate_eps;            /* floor of the arrival-rate estimate, > 0 */
+    int32_t sla_window;
+    int32_t d_regrow;
+} laps_awd_params;
+enum { LAPS_AWD_WAIT = 0, LAPS_AWD_DISPATCH = 1 };
+enum { LAPS_AWD_NONE = 0, LAPS_AWD_DEPTH = 1, LAPS_AWD_SLA = 2, LAPS_AWD_TMAX = 3, LAPS_AWD_WINDOW = 4 };
+int laps_awd_create(const laps_awd_params* p, double first_slack_us, laps_awd** out);
+void laps_awd_destroy(laps_awd* awd);
+double laps_awd_window_us(const laps_awd* awd);
+int32_t laps_awd_target_depth(const laps_awd* awd);
+/* The instance is free to form the next short batch from free_at_us on (e.g. when the dispatched step ends).
+ * Without this call the next round's timer may start at the dispatch itself.  EINVAL while a round collects. */
+int laps_awd_begin_round(laps_awd* awd, double free_at_us);
+/* One decision at now_us over the waiting short requests (host arrays [n_waiting], arrival order, all with
+ * arrival <= now).  The batch is re-formed at every poll: requests of the oldest one's length bucket first,
+ * then the others, passing over any that no captured shape within the budget would hold.
+ * *action = LAPS_AWD_DISPATCH: take_idx[0..*n_take) index the batch in the caller's arrays, to run in the
+ * captured shape (*len_bucket, *depth) (*depth >= *n_take); *reason says why; W and D are already updated.
+ * *action = LAPS_AWD_WAIT: poll again at *wake_us (INFINITY if the queue is empty) or at the next arrival.
+ * take_idx must hold n_waiting entries.  EINVAL on NULL / NaN / unordered arrivals / lengths outside the grid. */
+int laps_awd_poll(laps_awd* awd, double now_us, double rate_hat, int32_t n_waiting, const double* arrival_us,
+                  const double* ddl_us, const int32_t* new_len, int32_t* action, int32_t* n_take, int32_t* take_idx,
+                  int32_t* len_bucket, int32_t* depth, int32_t* reason, double* wake_us);
+
 const char* laps_last_error(void);
 const char* laps_version(void);
 

@@ -1,0 +1,34 @@
+"""Oracle for the compute / memory latency model and its boundaries.  TEST INFRASTRUCTURE ONLY.
+
+Section 2.1 of the paper: T_comp = alpha L (L + 2H) + beta L, T_mem = gamma_w L + gamma_r H; the boundary
+is the length at which the two are equal.  Instead of the printed closed forms, this oracle solves
+T_comp(L) - T_mem(L) = 0 numerically as a polynomial (numpy.roots) and fits the coefficients with
+numpy.linalg.lstsq, so that the library's closed forms and normal equations are checked against
+independent routines.  Pins (tests/test_latency_model.py): worked values computed by hand from the
+printed formulas, the H = 0 reduction, the large-H limit gamma_r / (2 alpha), T_comp == T_mem at the root.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def t_comp(alpha, beta, L, H):
+    return alpha * L * (L + 2.0 * H) + beta * L
+
+
+def t_mem(gamma_w, gamma_r, L, H):
+    return gamma_w * L + gamma_r * H
+
+
+def boundary(alpha, beta, gamma_w, gamma_r, H):
+    """Largest non-negative real L with T_comp(L,H) = T_mem(L,H); 0 if there is none."""
+    roots = np.roots([alpha, 2.0 * alpha * H + beta - gamma_w, -gamma_r * H])
+    real = [float(r.real) for r in roots if abs(r.imag) < 1e-12 and r.real > 0]
+    return max(real) if real else 0.0
+
+
+def fit(L, H, tc, tm):
+    L, H, tc, tm = (np.asarray(a, np.float64) for a in (L, H, tc, tm))
+    ab, *_ = np.linalg.lstsq(np.stack([L * (L + 2 * H), L], 1), tc, rcond=None)
+    gg, *_ = np.linalg.lstsq(np.stack([L, H], 1), tm, rcond=None)
+    return float(ab[0]), float(ab[1]), float(gg[0]), float(gg[1])

@@ -63,6 +63,10 @@ def lib():
             getattr(L, "laps_plan_" + name).argtypes = [C.c_void_p]
         for name in ("n_requests", "n_batches", "n_long"):
             getattr(L, "laps_plan_" + name).argtypes = [C.c_void_p]
+        L.laps_lm_boundary_prefill.restype = C.c_double
+        L.laps_lm_boundary_prefill.argtypes = [C.c_double] * 3
+        L.laps_lm_boundary_reprefill.restype = C.c_double
+        L.laps_lm_boundary_reprefill.argtypes = [C.c_double] * 5
         L.laps_plan_free.argtypes = [C.c_void_p]
         L.laps_ctx_destroy.argtypes = [C.c_void_p]
         L.laps_graph_destroy.argtypes = [C.c_void_p]
@@ -124,6 +128,97 @@ def laps_plan_buckets(short_max_len, len_buckets, depths, token_budget, long_chu
                 "req_batch": arr("req_batch", n), "req_row": arr("req_row", n)}
     finally:
         L.laps_plan_free(h)
+
+
+# --------------------------------------------------------------------------- latency model
+def laps_lm_boundary_prefill(alpha, beta, gamma_w) -> float:
+    return float(lib().laps_lm_boundary_prefill(alpha, beta, gamma_w))
+
+
+def laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len) -> float:
+    return float(lib().laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len))
+
+
+def laps_lm_fit(new_len, hist_len, t_comp, t_mem):
+    """Returns (alpha, beta, gamma_w, gamma_r)."""
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (new_len, hist_len, t_comp, t_mem)]
+    n = len(arrs[0])
+    assert all(len(a) == n for a in arrs)
+    out = (C.c_double * 4)()
+    ptrs = [a.ctypes.data_as(C.POINTER(C.c_double)) for a in arrs]
+    _check(lib().laps_lm_fit(C.c_int32(n), *ptrs, out))
+    return tuple(float(v) for v in out)
+
+
+# --------------------------------------------------------------------------- adaptive wait-depth batching
+class _AwdParams(C.Structure):
+    _fields_ = [("n_len_buckets", C.c_int32), ("len_buckets", C.POINTER(C.c_int32)), ("n_depths", C.c_int32),
+                ("depths", C.POINTER(C.c_int32)), ("mem_budget", C.c_int64), ("sigma_us", C.c_double),
+                ("w_min_us", C.c_double), ("w_max_us", C.c_double), ("s_hat_us", C.c_double), ("t_max_us", C.c_double),
+                ("delta_us", C.c_double), ("rate_eps", C.c_double), ("sla_window", C.c_int32), ("d_regrow", C.c_int32)]
+
+
+AWD_REASONS = ("none", "depth", "sla", "tmax", "window")
+
+
+class LapsAwd:
+    """Handle of the host-side AWD state (laps_awd_*): marshalling only."""
+
+    def __init__(self, len_buckets, depths, mem_budget, sigma_us=0.0, w_min_us=0.0, w_max_us=10_000.0, s_hat_us=1_000.0,
+                 t_max_us=float("inf"), delta_us=0.0, rate_eps=1e-9, sla_window=False, d_regrow=False,
+                 first_slack_us=float("inf")):
+        L = lib()
+        L.laps_awd_window_us.restype = C.c_double
+        L.laps_awd_window_us.argtypes = [C.c_void_p]
+        L.laps_awd_target_depth.restype = C.c_int32
+        L.laps_awd_target_depth.argtypes = [C.c_void_p]
+        L.laps_awd_destroy.restype = None
+        L.laps_awd_destroy.argtypes = [C.c_void_p]
+        L.laps_awd_begin_round.argtypes = [C.c_void_p, C.c_double]
+        (lb, lb_p), (dp, dp_p) = _i32(len_buckets), _i32(depths)
+        prm = _AwdParams(len(lb), lb_p, len(dp), dp_p, int(mem_budget), sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us, delta_us, rate_eps,
+                         int(sla_window), int(d_regrow))
+        self._h = C.c_void_p()
+        _check(L.laps_awd_create(C.byref(prm), C.c_double(first_slack_us), C.byref(self._h)))
+
+    @property
+    def window_us(self) -> float:
+        return float(lib().laps_awd_window_us(self._h))
+
+    @property
+    def target_depth(self) -> int:
+        return int(lib().laps_awd_target_depth(self._h))
+
+    def laps_awd_begin_round(self, free_at_us: float):
+        _check(lib().laps_awd_begin_round(self._h, C.c_double(free_at_us)))
+
+    def laps_awd_poll(self, now_us, arrival_us, ddl_us, new_len, rate_hat=0.0) -> dict:
+        arr = np.ascontiguousarray(arrival_us, dtype=np.float64)
+        ddl = np.ascontiguousarray(ddl_us, dtype=np.float64)
+        nl, nl_p = _i32(new_len)
+        n = len(arr)
+        assert len(ddl) == n and len(nl) == n
+        take = np.zeros(max(n, 1), np.int32)
+        action, n_take, lb, depth, reason = (C.c_int32() for _ in range(5))
+        wake = C.c_double()
+        dp = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+        _check(lib().laps_awd_poll(self._h, C.c_double(now_us), C.c_double(rate_hat), C.c_int32(n), dp(arr), dp(ddl), nl_p,
+                                   C.byref(action), C.byref(n_take), take.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   C.byref(lb), C.byref(depth),
+                                   C.byref(reason), C.byref(wake)))
+        return {"dispatch": action.value == 1, "take": [int(i) for i in take[:n_take.value]], "len_bucket": lb.value,
+                "depth": depth.value, "reason": AWD_REASONS[reason.value], "wake_us": wake.value}
+
+    def close(self):
+        if self._h:
+            lib().laps_awd_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # --------------------------------------------------------------------------- context

@@ -1,0 +1,63 @@
+// Compute / memory latency model of (re-)prefill and its boundary lengths (host only, double).
+//
+// Section 2.1 of the paper: T_comp(L,H) = alpha*L*(L+2H) + beta*L, T_mem(L,H) = gamma_w*L + gamma_r*H for
+// L new and H historical tokens; the boundary L_m is where the two are equal (closed forms for H = 0
+// and H > 0); the four coefficients are fitted at run time from samples (T_comp, T_mem, L, H).
+#include <cmath>
+#include <cstdint>
+
+#include "../../include/laps.h"
+
+void laps_set_error(const char* fmt, ...);
+
+extern "C" double laps_lm_boundary_prefill(double alpha, double beta, double gamma_w) {
+    if (!(alpha > 0.0)) return NAN;
+    const double v = (gamma_w - beta) / alpha;
+    return v > 0.0 ? v : 0.0;
+}
+
+extern "C" double laps_lm_boundary_reprefill(double alpha, double beta, double gamma_w, double gamma_r, double h) {
+    if (!(alpha > 0.0) || h < 0.0) return NAN;
+    // positive root of alpha L^2 + (2 alpha H + beta - gamma_w) L - gamma_r H = 0
+    const double b = 2.0 * alpha * h + beta - gamma_w;
+    const double disc = b * b + 4.0 * alpha * gamma_r * h;
+    if (disc < 0.0) return 0.0;
+    const double root = (-b + std::sqrt(disc)) / (2.0 * alpha);
+    return root > 0.0 ? root : 0.0;
+}
+
+// Two independent two-parameter least-squares problems through the origin (normal equations):
+//   t_comp ~ alpha * L(L+2H) + beta * L        t_mem ~ gamma_w * L + gamma_r * H
+static int fit2(int n, const double* x1, const double* x2, const double* y, double* c1, double* c2) {
+    double a11 = 0, a12 = 0, a22 = 0, b1 = 0, b2 = 0;
+    for (int i = 0; i < n; ++i) {
+        a11 += x1[i] * x1[i];
+        a12 += x1[i] * x2[i];
+        a22 += x2[i] * x2[i];
+        b1 += x1[i] * y[i];
+        b2 += x2[i] * y[i];
+    }
+    const double det = a11 * a22 - a12 * a12;
+    if (!(std::fabs(det) > 1e-12 * (a11 * a22 + 1e-300))) return 0;
+    *c1 = (b1 * a22 - b2 * a12) / det;
+    *c2 = (a11 * b2 - a12 * b1) / det;
+    return 1;
+}
+
+extern "C" int laps_lm_fit(int32_t n, const double* new_len, const double* hist_len, const double* t_comp,
+                           const double* t_mem, double* coef_out) {
+    if (n < 2 || !new_len || !hist_len || !t_comp || !t_mem || !coef_out) {
+        laps_set_error("lm_fit: need at least 2 samples and non-NULL arrays");
+        return LAPS_EINVAL;
+    }
+    double* q = new double[(size_t)n];
+    for (int i = 0; i < n; ++i) q[i] = new_len[i] * (new_len[i] + 2.0 * hist_len[i]);
+    const int ok1 = fit2(n, q, new_len, t_comp, &coef_out[0], &coef_out[1]);
+    const int ok2 = fit2(n, new_len, hist_len, t_mem, &coef_out[2], &coef_out[3]);
+    delete[] q;
+    if (!ok1 || !ok2) {
+        laps_set_error("lm_fit: samples do not determine the coefficients (vary L and H independently)");
+        return LAPS_EINVAL;
+    }
+    return LAPS_OK;
+}

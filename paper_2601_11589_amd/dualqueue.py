@@ -7,8 +7,12 @@ here for one GPU as: every GPU step is either the planned bucket batches of the 
 (each one captured-graph replay) or one chunk of the oldest long request; short requests are dispatched
 when the oldest has waited `window_us` or when `short_token_budget` padded tokens are waiting, otherwise
 the next long chunk runs.  When few tokens wait, the buckets are fused into the largest one needed (the
-paper's "graph fusion", Section 3.1): a replay then costs one pass over the weights whatever its shape.  The baseline is the policy the paper argues against (Section 2.3): one FCFS
-queue, each step a token-budget batch that mixes the next long chunk with whatever short requests fit.
+paper's "graph fusion", Section 3.1): a replay then costs one pass over the weights whatever its shape.
+`run_awd` replaces the fixed window by Adaptive-Wait-Depth batching (Algorithm 1, Section 3.2a): the
+library's laps_awd_* state decides when the short queue leaves and in which captured shape, one replay per
+dispatch; long chunks fill the time in which the short round is still collecting.
+The baseline is the policy the paper argues against (Section 2.3): one FCFS queue, each step a
+token-budget batch that mixes the next long chunk with whatever short requests fit.
 
 Arrivals are virtual timestamps; the clock advances by the measured GPU time of every step (HIP events
 around the step, host launch overhead included when it stalls the GPU) and jumps over idle gaps.
@@ -119,6 +123,10 @@ class DualQueue:
         plan = api.laps_plan_buckets(min(p.short_max_len, buckets[-1]), buckets, list(p.depths), p.short_token_budget,
                                      p.long_chunk, self.new_len[ids], self.prefix_len[ids])
         assert not plan["longs"]
+        return self._run_planned(ids, plan)
+
+    def _run_planned(self, ids, plan):
+        """Replays one captured graph per batch of `plan` (request ids local to `ids`)."""
         cu_local = np.concatenate([[0], np.cumsum(self.new_len[ids])])
         with torch.cuda.stream(self.stream):
             x_local = torch.cat([self.d_x[self.cu[r]: self.cu[r + 1]] for r in ids])
@@ -181,7 +189,7 @@ class DualQueue:
         done = np.zeros(self.n, np.int64)
         finish = np.zeros(self.n)
         t, busy, nxt = 0.0, 0.0, 0
-        kinds = {"short_graph": 0, "long_chunk": 0}
+        kinds = {"short_graph": 0, "long_chunk": 0, "short_busy_us": 0.0}
         q_s, q_l = [], []
         bucket_of = lambda r: next(lb for lb in p.len_buckets if lb >= self.new_len[r])
         while nxt < self.n or q_s or q_l:
@@ -198,6 +206,7 @@ class DualQueue:
                     t += us
                     busy += us
                     kinds["short_graph"] += 1
+                    kinds["short_busy_us"] += us
                     for r in ids:
                         done[r] = self.new_len[r]
                         finish[r] = t
@@ -219,6 +228,80 @@ class DualQueue:
                 t = max(t, min(wake))
         return DQResult(f"disaggregated(W={window:g}us)", t, busy, kinds["short_graph"] + kinds["long_chunk"], finish,
                         finish - arrival, kinds)
+
+    def run_awd(self, arrival_us, ddl_us=None, s_hat_us=2000.0, sigma_us=0.0, w_min_us=0.0, w_max_us=20000.0,
+                t_max_us=float("inf"), delta_us=0.0, sla_window=False, d_regrow=True, rate_ewma=0.2) -> DQResult:
+        """Temporal disaggregation with the short queue batched by laps_awd_*.  ddl_us: absolute deadlines of the
+        requests (None: deadline-free).  The arrival-rate estimate for the SLA window is an exponentially
+        weighted mean of the short inter-arrival gaps."""
+        p = self.p
+        arrival = np.asarray(arrival_us, np.float64)
+        ddl = np.full(self.n, np.inf) if ddl_us is None else np.asarray(ddl_us, np.float64)
+        order = list(np.argsort(arrival, kind="stable"))
+        known = [ddl[r] - s_hat_us for r in order if arrival[r] <= 0.0 and not self.is_long[r]]
+        awd = api.LapsAwd(p.len_buckets, p.depths, p.short_token_budget, sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us,
+                          delta_us, 1e-9, sla_window, d_regrow, first_slack_us=min(known, default=float("inf")))
+        done = np.zeros(self.n, np.int64)
+        finish = np.zeros(self.n)
+        t, busy, nxt = 0.0, 0.0, 0
+        kinds = {"short_graph": 0, "long_chunk": 0, "short_busy_us": 0.0}
+        reasons, depths_used = {}, []
+        q_s, q_l = [], []
+        gap, last_s = None, None
+        while nxt < self.n or q_s or q_l:
+            while nxt < self.n and arrival[order[nxt]] <= t:
+                r = order[nxt]
+                if self.is_long[r]:
+                    q_l.append(r)
+                else:
+                    if last_s is not None:
+                        g = arrival[r] - last_s
+                        gap = g if gap is None else (1 - rate_ewma) * gap + rate_ewma * g
+                    last_s = arrival[r]
+                    q_s.append(r)
+                nxt += 1
+            wake = float("inf")
+            if q_s:
+                rate = 1.0 / gap if gap else 0.0
+                dec = awd.laps_awd_poll(t, arrival[q_s], ddl[q_s], self.new_len[q_s], rate)
+                if dec["dispatch"]:
+                    ids = [q_s[j] for j in dec["take"]]
+                    q_s = [r for r in q_s if r not in set(ids)]
+                    plan = {"batches": [{"len_bucket": dec["len_bucket"], "depth": dec["depth"], "graph_ok": 1,
+                                         "req_ids": list(range(len(ids)))}]}
+                    (_, us), = self._run_planned(ids, plan)
+                    t += us
+                    busy += us
+                    kinds["short_graph"] += 1
+                    kinds["short_busy_us"] += us
+                    reasons[dec["reason"]] = reasons.get(dec["reason"], 0) + 1
+                    depths_used.append(len(ids))
+                    for r in ids:
+                        done[r] = self.new_len[r]
+                        finish[r] = t
+                    awd.laps_awd_begin_round(t)
+                    continue
+                wake = dec["wake_us"]
+            if q_l:
+                r = q_l[0]
+                c = int(min(self.new_len[r] - done[r], p.long_chunk))
+                us = self._run_varlen([(r, int(done[r]), c)])
+                t += us
+                busy += us
+                kinds["long_chunk"] += 1
+                done[r] += c
+                if done[r] == self.new_len[r]:
+                    finish[r] = t
+                    q_l.pop(0)
+            else:
+                nxt_arr = arrival[order[nxt]] if nxt < self.n else float("inf")
+                t = max(t, min(wake, nxt_arr))
+        kinds["dispatch_reasons"] = reasons
+        kinds["mean_short_depth"] = float(np.mean(depths_used)) if depths_used else 0.0
+        kinds["final_W_us"], kinds["final_D"] = awd.window_us, awd.target_depth
+        awd.close()
+        mode = "awd(" + ("sla-window" if sla_window else "adaptive") + ")"
+        return DQResult(mode, t, busy, kinds["short_graph"] + kinds["long_chunk"], finish, finish - arrival, kinds)
 
     def close(self):
         self.short.close()

@@ -238,12 +238,18 @@ def model8():
     ctx.close()
 
 
-def test_config5_dual_queue_step_loop(model8):
-    """4 long prompts + 512 short / re-prefill requests on an 8-layer stack: temporal disaggregation
-    (short buckets as graphs, long chunks) and the unified mixed-batch baseline both reproduce the
-    oracle on sampled requests; every request completes exactly once."""
+class Config5State:
+    pass
+
+
+@pytest.fixture(scope="module")
+def config5(model8):
+    """configs[4] resident in HBM: 4 long prompts + 512 short / re-prefill requests on the 8-layer stack, with
+    four sampled requests (3 short + the shortest long) whose prefix KV is seeded from the host so that the
+    oracle can follow them."""
     from paper_2601_11589_amd import dualqueue
     cfg, ctx, host_layers, dev_layers = model8
+    st = Config5State()
     seed = inputs.SEED_BASE + 5
     b = inputs.make_batch(5)
     x = inputs.make_activations(cfg, seed, b.n_tokens)
@@ -270,28 +276,56 @@ def test_config5_dual_queue_step_loop(model8):
         ctx.laps_kv_scatter(torch.from_numpy(pcu).cuda(), torch.zeros(len(sample), dtype=torch.int32, device="cuda"),
                             d_pt_sample, api.bf16_tensor(kk), api.bf16_tensor(vv), k_pools[l], v_pools[l])
     torch.cuda.synchronize()
-    dq = dualqueue.DualQueue(ctx, dev_layers, b.new_len, b.prefix_len, b.page_table, d_x, k_pools, v_pools,
-                             dualqueue.DQParams(), keep_outputs=True)
+    st.dq = dualqueue.DualQueue(ctx, dev_layers, b.new_len, b.prefix_len, b.page_table, d_x, k_pools, v_pools,
+                                dualqueue.DQParams(), keep_outputs=True)
+    st.b, st.is_long, st.sub, st.seed, st.cache, st.unified_makespan_us = b, is_long, sub, seed, {}, None
+    st.sampled_rows = lambda: np.concatenate([st.dq.out[cu_all[i]:cu_all[i + 1]].cpu().numpy() for i in sample])
+    yield st
+    st.dq.close()
+
+
+def test_config5_dual_queue_step_loop(config5):
+    """Temporal disaggregation (short buckets as graphs, long chunks) and the unified mixed-batch baseline both
+    reproduce the oracle on sampled requests; every request completes exactly once."""
+    st, dq, b, is_long = config5, config5.dq, config5.b, config5.is_long
     zeros = np.zeros(b.n)
-    cache = {}
-
-    def sampled_rows():
-        return np.concatenate([dq.out[cu_all[i]:cu_all[i + 1]].cpu().numpy() for i in sample])
-
     rd = dq.run_disaggregated(zeros, window_us=0.0)
-    assert_parity("config5 disaggregated (3 short + shortest long)", sampled_rows(), sub, None, cache)
+    assert_parity("config5 disaggregated (3 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
     dq.out.zero_()
     ru = dq.run_unified(zeros)
-    assert_parity("config5 unified mixed batches (same requests)", sampled_rows(), sub, None, cache)
+    assert_parity("config5 unified mixed batches (same requests)", st.sampled_rows(), st.sub, None, st.cache)
     for r in (rd, ru):
         assert np.all(r.finish_us > 0) and np.all(r.latency_us > 0)
         print("[config5]", r.summary(b.new_len, is_long), flush=True)
     assert rd.step_kinds["long_chunk"] == int(sum(-(-int(l) // 2048) for l in b.new_len[is_long]))
+    st.unified_makespan_us = ru.makespan_us
     # Poisson arrivals at 0.7 of the unified back-to-back service rate: both policies still finish everything
-    arr = inputs.poisson_arrivals_us(seed, b.n, 0.7 * b.n / (ru.makespan_us * 1e-6)).astype(np.float64)
+    arr = inputs.poisson_arrivals_us(st.seed, b.n, 0.7 * b.n / (ru.makespan_us * 1e-6)).astype(np.float64)
     rd2 = dq.run_disaggregated(arr, window_us=1000.0)
     ru2 = dq.run_unified(arr)
     for r in (rd2, ru2):
         assert np.all(r.finish_us >= arr) and r.makespan_us >= arr.max()
         print("[config5 poisson]", r.summary(b.new_len, is_long), flush=True)
-    dq.close()
+
+
+def test_config5_awd_policy(config5):
+    """The short queue batched by the library's Adaptive-Wait-Depth state (Algorithm 1): one captured graph per
+    dispatch, mixed buckets padded to the largest one; sampled outputs reproduce the oracle, every request
+    completes once, and under Poisson arrivals with deadlines the SLA trigger fires before the deadline passes."""
+    st, dq, b, is_long = config5, config5.dq, config5.b, config5.is_long
+    dq.out.zero_()
+    ra = dq.run_awd(np.zeros(b.n))
+    assert_parity("config5 AWD deadline-free (3 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
+    assert np.all(ra.finish_us > 0)
+    assert ra.step_kinds["long_chunk"] == int(sum(-(-int(l) // 2048) for l in b.new_len[is_long]))
+    assert ra.step_kinds["dispatch_reasons"].get("depth", 0) >= 1          # all waiting at t=0: rounds fill D at once
+    print("[config5 awd]", ra.summary(b.new_len, is_long), flush=True)
+    base = st.unified_makespan_us or ra.makespan_us
+    arr = inputs.poisson_arrivals_us(st.seed, b.n, 0.7 * b.n / (base * 1e-6)).astype(np.float64)
+    ddl = arr + 60_000.0
+    for sla_window in (False, True):
+        r = dq.run_awd(arr, ddl_us=ddl, s_hat_us=3000.0, sigma_us=1000.0, w_min_us=200.0, w_max_us=10_000.0,
+                       t_max_us=30_000.0, delta_us=500.0, sla_window=sla_window)
+        assert np.all(r.finish_us >= arr) and r.makespan_us >= arr.max()
+        assert 200.0 <= r.step_kinds["final_W_us"] <= 10_000.0 and r.step_kinds["final_D"] >= 1
+        print("[config5 awd poisson]", r.summary(b.new_len, is_long), flush=True)
