@@ -15,6 +15,14 @@
 // permutation key(8a + 4h + b) = 16(a/2) + 8h + 4(a%2) + b, which makes the eight probabilities a
 // lane holds in accumulator registers 8u..8u+7 exactly the eight consecutive keys its P fragment
 // must supply to the second product - no shuffles between the two MFMA stages.
+//
+// Few query rows over a long cached prefix (a short re-prefill turn) would leave most of the chip idle:
+// one request of 16 new tokens is a single row block per kv head.  For such launches the key range is
+// split over gridDim.z workgroups (at least 4 key tiles each); every split writes its un-normalised
+// accumulator with its running maximum and row sum, and a second kernel merges the splits in a fixed
+// order, so the result does not depend on scheduling.  The split count is a function of launch shapes
+// only (row blocks, kv heads, page-table width), which keeps captured graphs replayable; how many of
+// the splits a given sequence really uses is decided on the device from its length.
 #include "laps_internal.h"
 
 namespace {
@@ -24,9 +32,11 @@ constexpr int KT = 64;      // keys per tile (4 pages)
 __device__ __forceinline__ int swz8(int row, int c) { return c ^ ((row & 7) ^ ((row >> 3) & 1)); }
 __device__ __forceinline__ int swz16(int row, int c) { return c ^ (row & 15); }
 
-// per-sequence number of query-row blocks and their exclusive prefix sum (single workgroup)
+// per-sequence number of query-row blocks, their exclusive prefix sum, and the sequence of every work item
+// (single workgroup).  The item table spares each attention workgroup a chain of dependent loads.
 __global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__ new_len, int n_seq, int group,
-                                                          int rows_per_wg, int* __restrict__ tile_start) {
+                                                          int rows_per_wg, int* __restrict__ tile_start,
+                                                          int* __restrict__ item_seq, int max_items) {
     __shared__ int buf[256];
     __shared__ int carry;
     if (threadIdx.x == 0) carry = 0;
@@ -43,7 +53,11 @@ __global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__
             __syncthreads();
         }
         const int c = carry;
-        if (i < n_seq) tile_start[i] = c + buf[threadIdx.x] - v;
+        if (i < n_seq) {
+            const int first = c + buf[threadIdx.x] - v;
+            tile_start[i] = first;
+            for (int k = 0; k < v && first + k < max_items; ++k) item_seq[first + k] = i;   // bound: lengths that disagree with the row offsets must not write past the table
+        }
         __syncthreads();
         if (threadIdx.x == 255) carry = c + buf[255];
         __syncthreads();
@@ -53,15 +67,29 @@ __global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__
 
 // NW waves per workgroup, one 32-row query tile per wave: rows per workgroup = 32 * NW.  With NW = 8
 // two waves share a SIMD, so one wave's softmax (VALU, exp) overlaps the other's MFMAs.
-template <int HD, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out,
+// key tiles per split (lower bound) and the split geometry shared by the attention and the merge kernel
+constexpr int MIN_TILES_PER_SPLIT = 4;
+__device__ __forceinline__ void split_geometry(int kv_end, int n_split, int* eff, int* per) {
+    const int nt = (kv_end + KT - 1) / KT;
+    int e = nt / MIN_TILES_PER_SPLIT;
+    e = e < 1 ? 1 : (e > n_split ? n_split : e);
+    *eff = e;
+    *per = (nt + e - 1) / e;
+}
+
+// Two waves per SIMD in every variant (second launch-bound argument): with 4 waves per workgroup that is two
+// resident workgroups per compute unit, which the key-streaming launches need to cover the memory latency.
+template <int HD, int NW, bool SPLIT>
+__global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ out,
+                                                        float* __restrict__ part_o, float* __restrict__ part_ml,
                                                         const bf16_t* __restrict__ k_pool,
                                                         const bf16_t* __restrict__ v_pool,
                                                         const int* __restrict__ row_start,
                                                         const int* __restrict__ new_len,
                                                         const int* __restrict__ prefix_len,
                                                         const int* __restrict__ page_table, int max_pages,
-                                                        const int* __restrict__ tile_start, int n_seq, int n_q,
+                                                        const int* __restrict__ tile_start,
+                                                        const int* __restrict__ item_seq, int n_seq, int n_q,
                                                         int n_kv, float scale_log2e) {
     constexpr int NTHR = NW * 64;
     constexpr int CPR = HD / 8;            // 16-byte chunks per K row
@@ -77,12 +105,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
 
     const int item = blockIdx.x;
     if (item >= tile_start[n_seq]) return;
-    int lo = 0, hi = n_seq;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (tile_start[mid] <= item) lo = mid; else hi = mid;
-    }
-    const int seq = lo;
+    const int seq = item_seq[item];
     const int qtile = item - tile_start[seq];
     const int kvh = blockIdx.y;
     const int G = n_q / n_kv;
@@ -93,7 +116,16 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
     const int R0 = qtile * ROWS;
     if (R0 >= n_rows) return;
     const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
-    const int kv_end = H + last_row_wg / G + 1;  // keys visible to the last row of this block
+    const int kv_end_all = H + last_row_wg / G + 1;  // keys visible to the last row of this block
+    int kv_begin = 0, kv_end = kv_end_all, eff = 1;
+    if (SPLIT) {
+        int per;
+        split_geometry(kv_end_all, (int)gridDim.z, &eff, &per);
+        const int z = blockIdx.z;
+        if (z >= eff || z * per * KT >= kv_end_all) return;   // this split has no keys: the merge skips it too
+        kv_begin = z * per * KT;
+        kv_end = (z + 1) * per * KT < kv_end_all ? (z + 1) * per * KT : kv_end_all;
+    }
     const int* pt = page_table + (size_t)seq * max_pages;
     const size_t tok0 = (size_t)row_start[seq];
     const int q_stride = n_q * HD;
@@ -123,15 +155,24 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
     float m_run = -INFINITY, l_run = 0.f;   // running max (in log2 units, already scaled) and partial row sum
 
     // ---- tile copy assignment: chunk c = tid + i*NTHR of the tile's 4 pages
+    // The page ids of a tile are fetched one step before its data, so that the two dependent loads (table entry,
+    // then the page itself) do not add up on the critical path of every tile.
     u32x4 kreg[NLD], vreg[NLD];
-    auto load_tile = [&](int j0) {
+    int pgn[NLD];
+    auto load_pages = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            int pidx = j0 / LAPS_PAGE + (tid + i * NTHR) / CPP;
+            pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
+            pgn[i] = pt[pidx];
+        }
+    };
+    auto load_tile = [&](int j0) {   // uses the ids load_pages(j0) fetched
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int c = tid + i * NTHR;
-            const int pi = c / CPP, within = c % CPP;
-            int pidx = j0 / LAPS_PAGE + pi;
-            pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
-            const int pg = pt[pidx];
+            const int within = c % CPP;
+            const int pg = pgn[i];
             const size_t page = (size_t)(pg > 0 ? pg : 0);  // an unset (-1) entry must not turn into a wild address
             const size_t off = ((page * n_kv + kvh) * CPP + within);
             kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
@@ -170,17 +211,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
     const int ra = lm >> 3, rh = (lm >> 2) & 1, rb = lm & 3;
     const int krow = 16 * (ra >> 1) + 8 * rh + 4 * (ra & 1) + rb;
 
-    load_tile(0);
-    store_tile(0, 0);
-    if (KT < kv_end) load_tile(KT);
-    __syncthreads();
-    int buf = 0;
-    for (int j0 = 0; j0 < kv_end; j0 += KT, buf ^= 1) {
-        // stage the next tile (already in registers) into the other buffer, refill the registers
-        if (j0 + KT < kv_end) {
-            store_tile(j0 + KT, buf ^ 1);
-            if (j0 + 2 * KT < kv_end) load_tile(j0 + 2 * KT);
-        }
+    auto compute_tile = [&](int j0, int buf) {
         if (j0 <= vis_max) {  // wave-uniform: something of this tile is visible to this wave
             // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key sub-tiles)
             f32x16 s[2];
@@ -216,7 +247,10 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[sub][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx * scale_log2e);  // finite from the first tile on (key 0 is visible)
+            // un-split: finite from the first tile on (key 0 is visible to every row).  A later split can start
+            // on a diagonal tile in which a row sees nothing yet: keep exp2(-inf - -inf) out of the arithmetic.
+            const float m_new = fmaxf(m_run, mx * scale_log2e);
+            const float m_sub = (SPLIT && m_new == -INFINITY) ? 0.f : m_new;
             bf16x8 pf[2][2];
             float psum = 0.f;
 #pragma unroll
@@ -226,14 +260,14 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
                     bf16x8 pk;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + e], scale_log2e, -m_new));
+                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + e], scale_log2e, -m_sub));
                         psum += p;
                         pk[e] = (__bf16)p;
                     }
                     pf[sub][u] = pk;
                 }
             if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
                 l_run *= alpha;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
@@ -253,12 +287,57 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
                 }
             }
         }
+    };
+    load_pages(kv_begin);
+    load_tile(kv_begin);
+    load_pages(kv_begin + KT);        // indices are clamped to the sequence's pages: harmless past the end
+    store_tile(kv_begin, 0);
+    if (kv_begin + KT < kv_end) {
+        load_tile(kv_begin + KT);
+        load_pages(kv_begin + 2 * KT);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int j0 = kv_begin; j0 < kv_end; j0 += KT, buf ^= 1) {
+        // stage the next tile (already in registers) into the other buffer, refill the registers.  (A second
+        // register set, two tiles in flight, spills at head_dim 128: the landing registers are the limit.)
+        if (j0 + KT < kv_end) {
+            store_tile(j0 + KT, buf ^ 1);
+            if (j0 + 2 * KT < kv_end) {
+                load_tile(j0 + 2 * KT);
+                load_pages(j0 + 3 * KT);
+            }
+        }
+        compute_tile(j0, buf);
         __syncthreads();
     }
 
     // ---- normalise and store: lane owns row r; register i of sub-tile ni is head_dim index
     //      ni*32 + 8*(i/4) + 4*(lane/32) + i%4
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (SPLIT && eff > 1) {
+        // partial result of this key range: accumulator as [4-float chunk][row] so that the 32 rows of a half
+        // wave write consecutive 16-byte pieces; (running max, row sum) per row
+        if (row_id < n_rows) {
+            const size_t blk = ((size_t)item * n_kv + kvh) * gridDim.z + blockIdx.z;
+            const int row = wave * 32 + lm;
+            f32x4* po = reinterpret_cast<f32x4*>(part_o) + blk * (size_t)(HD / 4) * ROWS;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 w;
+                    w.x = o[ni][4 * a]; w.y = o[ni][4 * a + 1]; w.z = o[ni][4 * a + 2]; w.w = o[ni][4 * a + 3];
+                    po[(size_t)(ni * 8 + 2 * a + lh) * ROWS + row] = w;
+                }
+            if (lh == 0) {
+                float* pm = part_ml + blk * (size_t)(2 * ROWS);
+                pm[row] = m_run;
+                pm[ROWS + row] = l_tot;
+            }
+        }
+        return;
+    }
     if (row_id < n_rows) {
         const float inv = 1.f / l_tot;
         bf16_t* op = out + (tok0 + tq) * q_stride + (size_t)(kvh * G + gq) * HD;
@@ -274,23 +353,151 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const bf16_t* __restrict_
     }
 }
 
+// Merges the key-range splits of attn_kernel<.., SPLIT = true> in a fixed order: out = sum_z 2^(m_z - M) O_z /
+// sum_z 2^(m_z - M) l_z with M = max_z m_z.  A workgroup covers the 128 rows of one work item and one 4-float
+// slice of head_dim; its four groups of 128 threads take the splits z = g, g + 4, g + 8, ... (more loads in flight than one
+// thread per row could issue) and their four partial sums are added in the order g = 0, 1, 2, 3.
+constexpr int MERGE_GROUPS = 4;
+template <int HD>
+__global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
+    bf16_t* __restrict__ out, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+    const int* __restrict__ row_start, const int* __restrict__ new_len, const int* __restrict__ prefix_len,
+    const int* __restrict__ tile_start, const int* __restrict__ item_seq, int n_seq, int n_q, int n_kv, int n_split) {
+    constexpr int ROWS = 128;
+    __shared__ float red_m[MERGE_GROUPS][ROWS];
+    __shared__ float red_l[MERGE_GROUPS][ROWS];
+    __shared__ f32x4 red_o[MERGE_GROUPS][ROWS];
+    const int item = blockIdx.x;
+    if (item >= tile_start[n_seq]) return;
+    const int seq = item_seq[item], qtile = item - tile_start[seq], kvh = blockIdx.y;
+    const int G = n_q / n_kv;
+    const int L = new_len[seq], H = prefix_len[seq];
+    const int n_rows = L * G, R0 = qtile * ROWS;
+    if (R0 >= n_rows) return;
+    const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
+    const int kv_end_all = H + last_row_wg / G + 1;
+    int eff, per;
+    split_geometry(kv_end_all, n_split, &eff, &per);
+    if (eff == 1) return;   // the attention kernel wrote the final rows itself (uniform over the workgroup)
+    const int nt = (kv_end_all + KT - 1) / KT;
+    const int used = (nt + per - 1) / per < eff ? (nt + per - 1) / per : eff;   // splits that had keys
+    const int row = threadIdx.x % ROWS, g = threadIdx.x / ROWS, row_id = R0 + row;
+    const bool live = row_id < n_rows;
+    const size_t blk0 = ((size_t)item * n_kv + kvh) * n_split;
+    const float* pm = part_ml + blk0 * (size_t)(2 * ROWS) + row;
+    // every load below is independent of the others: unrolled so that many are in flight at once
+    float m_g = -INFINITY;
+    if (live) {
+#pragma unroll 4
+        for (int z = g; z < used; z += MERGE_GROUPS) m_g = fmaxf(m_g, pm[(size_t)z * 2 * ROWS]);
+    }
+    red_m[g][row] = m_g;
+    __syncthreads();
+    float m_all = red_m[0][row];
+#pragma unroll
+    for (int k = 1; k < MERGE_GROUPS; ++k) m_all = fmaxf(m_all, red_m[k][row]);
+    const int c = blockIdx.z;   // one 4-float chunk of head_dim per workgroup
+    const f32x4* po = reinterpret_cast<const f32x4*>(part_o) + (blk0 * (size_t)(HD / 4) + c) * ROWS + row;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l_g = 0.f;
+    if (live) {
+#pragma unroll 4
+        for (int z = g; z < used; z += MERGE_GROUPS) {
+            const float w = __builtin_amdgcn_exp2f(pm[(size_t)z * 2 * ROWS] - m_all);
+            const f32x4 v = po[(size_t)z * (HD / 4) * ROWS];
+            l_g = __builtin_fmaf(w, pm[(size_t)z * 2 * ROWS + ROWS], l_g);
+            acc.x = __builtin_fmaf(w, v.x, acc.x);
+            acc.y = __builtin_fmaf(w, v.y, acc.y);
+            acc.z = __builtin_fmaf(w, v.z, acc.z);
+            acc.w = __builtin_fmaf(w, v.w, acc.w);
+        }
+    }
+    red_l[g][row] = l_g;
+    red_o[g][row] = acc;
+    __syncthreads();
+    if (g != 0 || !live) return;
+    float l_all = red_l[0][row];
+    f32x4 o4 = red_o[0][row];
+#pragma unroll
+    for (int k = 1; k < MERGE_GROUPS; ++k) {
+        l_all += red_l[k][row];
+        const f32x4 t = red_o[k][row];
+        o4.x += t.x; o4.y += t.y; o4.z += t.z; o4.w += t.w;
+    }
+    const float inv = 1.f / l_all;
+    const int tq = row_id / G, gq = row_id - tq * G;
+    bf16_t* op = out + ((size_t)row_start[seq] + tq) * (size_t)(n_q * HD) + (size_t)(kvh * G + gq) * HD;
+    u32x2 o2;
+    o2.x = pack_bf16x2(o4.x * inv, o4.y * inv);
+    o2.y = pack_bf16x2(o4.z * inv, o4.w * inv);
+    *reinterpret_cast<u32x2*>(op + 4 * c) = o2;
+}
+
 template <int HD, int NW>
 int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool, const int* row_start,
                 const int* new_len, const int* prefix_len, const int* page_table, int max_pages, const int* tile_start,
-                int n_seq, int max_items, int n_q, int n_kv, hipStream_t s) {
+                const int* item_seq, int n_seq, int max_items, int n_q, int n_kv, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
-    hipLaunchKernelGGL((attn_kernel<HD, NW>), dim3(max_items, n_kv), dim3(NW * 64), 0, s, q, out, k_pool, v_pool,
-                       row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, n_q, n_kv, scale_log2e);
+    hipLaunchKernelGGL((attn_kernel<HD, NW, false>), dim3(max_items, n_kv), dim3(NW * 64), 0, s, q, out, nullptr, nullptr,
+                       k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
+                       n_q, n_kv, scale_log2e);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
+
+template <int HD>
+int launch_attn_split(const bf16_t* q, bf16_t* out, float* part, const bf16_t* k_pool, const bf16_t* v_pool,
+                      const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
+                      int max_pages, const int* tile_start, const int* item_seq, int n_seq, int max_items, int n_split,
+                      int n_q, int n_kv, hipStream_t s) {
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+    const size_t blocks = (size_t)max_items * n_kv * n_split;
+    float* part_o = part;
+    float* part_ml = part + blocks * 128 * HD;
+    hipLaunchKernelGGL((attn_kernel<HD, 4, true>), dim3(max_items, n_kv, n_split), dim3(256), 0, s, q, out, part_o, part_ml,
+                       k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
+                       n_q, n_kv, scale_log2e);
+    LAPS_LAUNCH_CHECK();
+    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(max_items, n_kv, HD / 4), dim3(128 * MERGE_GROUPS), 0, s, out, part_o, part_ml,
+                       row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
 
 }  // namespace
 
-// Query-row blocking for a batch: rows per workgroup (128 or 256) and an upper bound on the number
-// of (sequence, row block) work items.  Depends only on shapes known to the host.
-static void attn_blocking(int n_seq, int n_tokens, int group, int* mt, int* max_items) {
+// Upper bound on the workgroups of a key-split launch, and the bytes of partial results it needs.
+static constexpr int kSplitTargetBlocks = 512;   // aim for two workgroups per compute unit
+static constexpr int kSplitBelowBlocks = 256;    // launches with fewer un-split workgroups than this are split
+static constexpr int kSplitMax = 64;
+
+size_t laps_attn_partial_bytes(int hd) {
+    // blocks0 < kSplitBelowBlocks and n_split <= ceil(kSplitTargetBlocks / blocks0) give fewer than
+    // kSplitTargetBlocks + kSplitBelowBlocks workgroups, each with 128 rows of (hd + 2) floats
+    return (size_t)(kSplitTargetBlocks + kSplitBelowBlocks) * 128 * (size_t)(hd + 2) * sizeof(float);
+}
+
+// Query-row blocking for a batch: rows per workgroup (128 or 256), an upper bound on the number of
+// (sequence, row block) work items, and the number of key-range splits.  Depends only on shapes known to
+// the host (a captured graph must replay with the same grid whatever the lengths staged into it).
+static void attn_blocking(int n_seq, int n_tokens, int group, int n_kv, int max_pages, int* mt, int* max_items,
+                          int* n_split) {
     const long total_rows = (long)n_tokens * group;
+    const long items1 = total_rows / 128 + n_seq;      // bound with 128-row blocks
+    const int max_kv_tiles = (max_pages * LAPS_PAGE + KT - 1) / KT;
+    *n_split = 1;
+    if (items1 * n_kv < kSplitBelowBlocks && max_kv_tiles >= 2 * MIN_TILES_PER_SPLIT) {
+        const int blocks0 = (int)items1 * n_kv;
+        int ns = (kSplitTargetBlocks + blocks0 - 1) / blocks0;
+        ns = ns < max_kv_tiles / MIN_TILES_PER_SPLIT ? ns : max_kv_tiles / MIN_TILES_PER_SPLIT;
+        ns = ns < kSplitMax ? ns : kSplitMax;
+        if (ns > 1) {
+            *n_split = ns;
+            *mt = 1;
+            *max_items = (int)items1;
+            return;
+        }
+    }
     *mt = (total_rows > 128L * n_seq) ? 2 : 1;  // average rows per sequence above one 128-row block
     const int rows_per_wg = 128 * *mt;
     // every sequence contributes ceil(rows/rows_per_wg) blocks: at most rows/rows_per_wg + 1
@@ -298,28 +505,41 @@ static void attn_blocking(int n_seq, int n_tokens, int group, int* mt, int* max_
 }
 
 // Work-item table for laps_launch_attention; depends on the batch only, so a layer stack builds it once.
-int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv,
-                           hipStream_t s) {
-    int mt, max_items;
-    attn_blocking(n_seq, n_tokens, n_q / n_kv, &mt, &max_items);
-    hipLaunchKernelGGL(attn_sched_kernel, dim3(1), dim3(256), 0, s, new_len, n_seq, n_q / n_kv, 128 * mt, tile_start);
+size_t laps_attn_item_table_bytes(int max_tokens, int max_seqs, int group) {
+    return ((size_t)max_tokens * group / 128 + max_seqs + 1) * sizeof(int);
+}
+
+int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_pages, int* tile_start, int* item_seq,
+                           int n_q, int n_kv, hipStream_t s) {
+    int mt, max_items, n_split;
+    attn_blocking(n_seq, n_tokens, n_q / n_kv, n_kv, max_pages, &mt, &max_items, &n_split);
+    hipLaunchKernelGGL(attn_sched_kernel, dim3(1), dim3(256), 0, s, new_len, n_seq, n_q / n_kv, 128 * mt, tile_start,
+                       item_seq, max_items);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
 
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
-                          int max_pages, int n_seq, int n_tokens, const int* tile_start, int n_q, int n_kv, int hd,
-                          hipStream_t s) {
-    int mt, max_items;
-    attn_blocking(n_seq, n_tokens, n_q / n_kv, &mt, &max_items);
+                          int max_pages, int n_seq, int n_tokens, const int* tile_start, const int* item_seq,
+                          float* partial, int n_q, int n_kv, int hd, hipStream_t s) {
+    int mt, max_items, n_split;
+    attn_blocking(n_seq, n_tokens, n_q / n_kv, n_kv, max_pages, &mt, &max_items, &n_split);
+    if (n_split > 1) {
+        if (!partial) {
+            laps_set_error("attention: key-split launch needs the partial-result workspace");
+            return LAPS_EINVAL;
+        }
+        if (hd == 128) return launch_attn_split<128>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, s);
+        if (hd == 64) return launch_attn_split<64>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, s);
+    }
     if (hd == 128) {
-        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
     }
     if (hd == 64) {
-        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
+        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
     }
     laps_set_error("attention: head_dim %d not supported (64 or 128)", hd);
     return LAPS_EINVAL;

@@ -37,7 +37,7 @@ struct laps_ctx {
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t tok_pos, tok_slot, new_len, tile_start, r, q, attn, act, x_mid, partial, total;
+    size_t tok_pos, tok_slot, new_len, tile_start, item_seq, r, q, attn, act, x_mid, partial, total;
 };
 
 static size_t partial_bytes_for(const laps_model_cfg& c, int m) {
@@ -60,6 +60,7 @@ static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs)
     w.tok_slot = o;   o += align256(M * 4);
     w.new_len = o;    o += align256((size_t)max_seqs * 4);
     w.tile_start = o; o += align256((size_t)(max_seqs + 1) * 4);
+    w.item_seq = o;   o += align256(laps_attn_item_table_bytes(max_tokens, max_seqs, c.n_q_heads / c.n_kv_heads));
     w.r = o;          o += align256(M * c.hidden * 2);
     w.q = o;          o += align256(M * qd * 2);
     w.attn = o;       o += align256(M * qd * 2);
@@ -75,6 +76,10 @@ static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs)
     }
     for (int m = 256; m < max_tokens; m += 256) {
         const size_t t = partial_bytes_for(c, m);
+        pb = t > pb ? t : pb;
+    }
+    {   // the same region holds the attention's key-split partial results (the two uses never overlap in time)
+        const size_t t = laps_attn_partial_bytes(c.head_dim);
         pb = t > pb ? t : pb;
     }
     w.partial = o;    o += align256(pb);
@@ -232,6 +237,7 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
     int* tok_slot = reinterpret_cast<int*>(ws + L.tok_slot);
     int* new_len = reinterpret_cast<int*>(ws + L.new_len);
     int* tile_start = reinterpret_cast<int*>(ws + L.tile_start);
+    int* item_seq = reinterpret_cast<int*>(ws + L.item_seq);
     bf16_t* r = reinterpret_cast<bf16_t*>(ws + L.r);
     bf16_t* q = reinterpret_cast<bf16_t*>(ws + L.q);
     bf16_t* attn = reinterpret_cast<bf16_t*>(ws + L.attn);
@@ -246,7 +252,7 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
     }
     {
         ProfScope ps(c, s, LAPS_K_PREP, capturing);
-        LAPS_TRY(laps_launch_attn_sched(new_len, b.n_seq, M, tile_start, cf.n_q_heads, cf.n_kv_heads, s));
+        LAPS_TRY(laps_launch_attn_sched(new_len, b.n_seq, M, b.max_pages, tile_start, item_seq, cf.n_q_heads, cf.n_kv_heads, s));
     }
     {
         ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
@@ -270,7 +276,7 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         {
             ProfScope ps(c, s, LAPS_K_ATTN, capturing);
             LAPS_TRY(laps_launch_attention(q, attn, kp, vp, b.row_start, new_len, b.prefix_len, b.page_table, b.max_pages,
-                                           b.n_seq, M, tile_start, cf.n_q_heads, cf.n_kv_heads, hd, s));
+                                           b.n_seq, M, tile_start, item_seq, partial, cf.n_q_heads, cf.n_kv_heads, hd, s));
         }
         // x_mid = resid + attn W_o^T ; r = rmsnorm(x_mid; ln2)
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), M, d, qd, EPI_RESID,
@@ -472,12 +478,13 @@ extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
     int* new_len = reinterpret_cast<int*>(w8 + L.new_len);
     LAPS_TRY(laps_launch_prep(n_tokens, n_seq, cu, seq_len, prefix_len, pt, max_pages, new_len,
                               reinterpret_cast<int*>(w8 + L.tok_pos), reinterpret_cast<int*>(w8 + L.tok_slot), s));
-    LAPS_TRY(laps_launch_attn_sched(new_len, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),
-                                    c->cfg.n_q_heads, c->cfg.n_kv_heads, s));
+    LAPS_TRY(laps_launch_attn_sched(new_len, n_seq, n_tokens, max_pages, reinterpret_cast<int*>(w8 + L.tile_start),
+                                    reinterpret_cast<int*>(w8 + L.item_seq), c->cfg.n_q_heads, c->cfg.n_kv_heads, s));
     return laps_launch_attention(static_cast<const bf16_t*>(q), static_cast<bf16_t*>(out),
                                  static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), cu, new_len,
                                  prefix_len, pt, max_pages, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),
-                                 c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.head_dim, s);
+                                 reinterpret_cast<int*>(w8 + L.item_seq), reinterpret_cast<float*>(w8 + L.partial), c->cfg.n_q_heads, c->cfg.n_kv_heads,
+                                 c->cfg.head_dim, s);
 }
 
 // ----------------------------------------------------------------------------- captured buckets

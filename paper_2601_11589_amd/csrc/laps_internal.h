@@ -79,9 +79,15 @@ int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, co
 int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s);
 
 // ----------------------------------------------------------------------------- attention
-int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int* tile_start, int n_q, int n_kv,
-                           hipStream_t s);
+// Both take the same (n_seq, n_tokens, max_pages): the blocking they derive from them must agree.
+// `partial` (laps_attn_partial_bytes, 16-byte aligned) receives per-split results when the launch shape
+// calls for splitting the key range; it may be NULL only if max_pages * 16 < 1024.
+// tile_start: n_seq + 1 ints; item_seq: laps_attn_item_table_bytes (sequence of every row-block work item).
+size_t laps_attn_partial_bytes(int hd);
+size_t laps_attn_item_table_bytes(int max_tokens, int max_seqs, int group);
+int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_pages, int* tile_start, int* item_seq,
+                           int n_q, int n_kv, hipStream_t s);
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
-                          int max_pages, int n_seq, int n_tokens, const int* tile_start, int n_q, int n_kv, int hd,
-                          hipStream_t s);
+                          int max_pages, int n_seq, int n_tokens, const int* tile_start, const int* item_seq,
+                          float* partial, int n_q, int n_kv, int hd, hipStream_t s);

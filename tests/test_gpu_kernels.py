@@ -106,6 +106,11 @@ def run_attention(ctx, cfg, c, prefix_len):
     ("tiny_many_row_blocks", inputs.tiny_cfg, [200, 70], [0, 130]),
     ("hd128_group5", lambda: inputs.qwen32b_cfg(1), [1, 16, 64, 40, 130], [0, 515, 100, 1, 64]),
     ("hd128_group5_short", lambda: inputs.qwen32b_cfg(1), [1, 16, 20, 8], [0, 515, 100, 1]),
+    # few query rows over long prefixes: the key range is split over workgroups and merged (5, 2, 4 and 1 splits)
+    ("tiny_key_split", inputs.tiny_cfg, [5, 16, 1, 64], [3000, 1100, 2047, 0]),
+    ("hd128_key_split", lambda: inputs.qwen32b_cfg(1), [16, 8, 33], [4100, 1500, 20]),
+    # 73 key tiles in 9 splits: the last split is one diagonal tile in which the first 30 tokens see no key
+    ("tiny_key_split_rows_without_keys", inputs.tiny_cfg, [64], [4578]),
 ])
 def test_attention_matches_oracle(name, cfgf, new_len, prefix_len):
     cfg = cfgf()
