@@ -258,6 +258,8 @@ typedef struct {
     int32_t n_depths;
     const int32_t* depths;      /* host, strictly ascending */
     int64_t mem_budget;         /* M, padded tokens; >= depths[0] * largest bucket */
+    int64_t fuse_budget;        /* padded tokens up to which requests of another length bucket than the oldest
+                                   one's may join the batch (shape of the largest bucket); < 0: mem_budget */
     double sigma_us;            /* slack trigger */
     double w_min_us, w_max_us;  /* 0 <= w_min <= w_max < inf */
     double s_hat_us;            /* service-time estimate of one short step */

@@ -23,7 +23,9 @@ Readings taken where the paper is silent (each also listed with the design notes
   * "bucket-first": among waiting requests (arrival order), those in the length bucket of the oldest one
     are taken first, then the others; a request that would push mem(NearestGraph) above M is skipped and
     stays queued;  the batch is re-formed from the waiting queue at every decision instant;
-  * a batch of mixed buckets runs in the shape of its largest bucket;
+  * a batch of mixed buckets runs in the shape of its largest bucket; requests of another bucket than the
+    oldest one's join only while the fused shape stays within `fuse_budget` padded tokens (the "graph fusion"
+    of Section 3.1 pays only while a step costs one pass over the weights whatever its shape);
   * r_hat is supplied by the caller (requests per microsecond) for the epoch;
   * optional growth of D (off in the printed algorithm, where D can only fall): when a round fills its
     target while at least as many requests again are still waiting, D moves to the next larger captured depth
@@ -57,6 +59,7 @@ class AwdParams:
     sla_window: bool = False        # Section 3.2a window instead of the adapted W
     rate_eps: float = 1e-9
     d_regrow: bool = False
+    fuse_budget: int = -1           # padded tokens up to which other length buckets may join (-1: mem_budget)
 
 
 def clip(v, lo, hi):
@@ -67,10 +70,11 @@ def bucket_of(p: AwdParams, n: int) -> int:
     return min(b for b in p.len_buckets if b >= n)
 
 
-def nearest_graph(p: AwdParams, len_bucket: int, depth: int):
+def nearest_graph(p: AwdParams, len_bucket: int, depth: int, budget=None):
     """Closest captured shape for a batch of `depth` rows of `len_bucket`: smallest captured depth >= depth
-    whose padded tokens fit M, or None."""
-    ok = [d for d in p.depths if d >= depth and d * len_bucket <= p.mem_budget]
+    whose padded tokens fit the budget (M unless given), or None."""
+    budget = p.mem_budget if budget is None else budget
+    ok = [d for d in p.depths if d >= depth and d * len_bucket <= budget]
     return (len_bucket, min(ok)) if ok else None
 
 
@@ -92,7 +96,10 @@ def form_batch(p: AwdParams, waiting, new_len, target_depth):
             nxt = r
             break
         lb = max(cur_len, bucket_of(p, new_len[r]))
-        if nearest_graph(p, lb, len(batch) + 1) is None:
+        budget = p.mem_budget
+        if bucket_of(p, new_len[r]) != head_bucket and p.fuse_budget >= 0:
+            budget = min(budget, p.fuse_budget)         # another bucket joins only while padding stays cheap
+        if nearest_graph(p, lb, len(batch) + 1, budget) is None:
             continue
         batch.append(r)
         cur_len = lb

@@ -153,7 +153,8 @@ def laps_lm_fit(new_len, hist_len, t_comp, t_mem):
 # --------------------------------------------------------------------------- adaptive wait-depth batching
 class _AwdParams(C.Structure):
     _fields_ = [("n_len_buckets", C.c_int32), ("len_buckets", C.POINTER(C.c_int32)), ("n_depths", C.c_int32),
-                ("depths", C.POINTER(C.c_int32)), ("mem_budget", C.c_int64), ("sigma_us", C.c_double),
+                ("depths", C.POINTER(C.c_int32)), ("mem_budget", C.c_int64), ("fuse_budget", C.c_int64),
+                ("sigma_us", C.c_double),
                 ("w_min_us", C.c_double), ("w_max_us", C.c_double), ("s_hat_us", C.c_double), ("t_max_us", C.c_double),
                 ("delta_us", C.c_double), ("rate_eps", C.c_double), ("sla_window", C.c_int32), ("d_regrow", C.c_int32)]
 
@@ -166,7 +167,7 @@ class LapsAwd:
 
     def __init__(self, len_buckets, depths, mem_budget, sigma_us=0.0, w_min_us=0.0, w_max_us=10_000.0, s_hat_us=1_000.0,
                  t_max_us=float("inf"), delta_us=0.0, rate_eps=1e-9, sla_window=False, d_regrow=False,
-                 first_slack_us=float("inf")):
+                 first_slack_us=float("inf"), fuse_budget=-1):
         L = lib()
         L.laps_awd_window_us.restype = C.c_double
         L.laps_awd_window_us.argtypes = [C.c_void_p]
@@ -176,7 +177,7 @@ class LapsAwd:
         L.laps_awd_destroy.argtypes = [C.c_void_p]
         L.laps_awd_begin_round.argtypes = [C.c_void_p, C.c_double]
         (lb, lb_p), (dp, dp_p) = _i32(len_buckets), _i32(depths)
-        prm = _AwdParams(len(lb), lb_p, len(dp), dp_p, int(mem_budget), sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us, delta_us, rate_eps,
+        prm = _AwdParams(len(lb), lb_p, len(dp), dp_p, int(mem_budget), int(fuse_budget), sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us, delta_us, rate_eps,
                          int(sla_window), int(d_regrow))
         self._h = C.c_void_p()
         _check(L.laps_awd_create(C.byref(prm), C.c_double(first_slack_us), C.byref(self._h)))

@@ -25,7 +25,7 @@ void laps_set_error(const char* fmt, ...);
 
 struct laps_awd {
     std::vector<int32_t> len_buckets, depths;
-    int64_t mem_budget;
+    int64_t mem_budget, fuse_budget;
     double sigma, w_min, w_max, s_hat, t_max, delta, rate_eps;
     bool sla_window, d_regrow;
     double window;          // W
@@ -51,9 +51,9 @@ int32_t bucket_of(const laps_awd* a, int32_t n) {
 }
 
 // smallest captured depth >= rows with len_bucket * depth within the budget, or 0
-int32_t nearest_depth(const laps_awd* a, int32_t len_bucket, int32_t rows) {
+int32_t nearest_depth(const laps_awd* a, int32_t len_bucket, int32_t rows, int64_t budget) {
     for (int32_t d : a->depths)
-        if (d >= rows) return (int64_t)d * len_bucket <= a->mem_budget ? d : 0;
+        if (d >= rows) return (int64_t)d * len_bucket <= budget ? d : 0;
     return 0;
 }
 
@@ -77,7 +77,9 @@ Batch form_batch(laps_awd* a, int32_t n_waiting, const int32_t* new_len, int32_t
                 break;
             }
             const int32_t lb = std::max(b.len_bucket, bk);
-            if (nearest_depth(a, lb, b.n + 1) == 0) continue;
+            // another bucket than the head's joins only while the fused shape stays within the fusion budget
+            const int64_t budget = pass == 0 ? a->mem_budget : std::min(a->mem_budget, a->fuse_budget);
+            if (nearest_depth(a, lb, b.n + 1, budget) == 0) continue;
             take_idx[b.n++] = i;
             b.len_bucket = lb;
         }
@@ -122,6 +124,7 @@ extern "C" int laps_awd_create(const laps_awd_params* p, double first_slack_us, 
     a->len_buckets.assign(p->len_buckets, p->len_buckets + p->n_len_buckets);
     a->depths.assign(p->depths, p->depths + p->n_depths);
     a->mem_budget = p->mem_budget;
+    a->fuse_budget = p->fuse_budget < 0 ? p->mem_budget : p->fuse_budget;
     a->sigma = p->sigma_us;
     a->w_min = p->w_min_us;
     a->w_max = p->w_max_us;
@@ -224,7 +227,7 @@ extern "C" int laps_awd_poll(laps_awd* a, double now_us, double rate_hat, int32_
     *action = LAPS_AWD_DISPATCH;
     *n_take = d;
     *len_bucket = b.len_bucket;
-    *depth = nearest_depth(a, b.len_bucket, d);
+    *depth = nearest_depth(a, b.len_bucket, d, a->mem_budget);
     *reason = why;
     if (d >= a->target_depth) {
         a->window = clipd(tau, a->w_min, a->w_max);

@@ -37,7 +37,8 @@ class DQParams:
     long_chunk: int = 2048             # C_l
     unified_budget: int = 2048         # tokens per step of the unified baseline
     window_us: float = 1000.0          # fixed waiting window W
-    merge_below: int = 512             # graph fusion: below this many waiting padded tokens (where a replay
+    fuse_budget: int = 128             # AWD: other length buckets join a batch only up to this many padded tokens
+    merge_below: int = 128             # graph fusion: below this many waiting padded tokens (where a replay
                                        # costs one pass over the weights whatever its shape) all waiting short
                                        # requests share the largest needed length bucket: one replay, not three
 
@@ -240,7 +241,8 @@ class DualQueue:
         order = list(np.argsort(arrival, kind="stable"))
         known = [ddl[r] - s_hat_us for r in order if arrival[r] <= 0.0 and not self.is_long[r]]
         awd = api.LapsAwd(p.len_buckets, p.depths, p.short_token_budget, sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us,
-                          delta_us, 1e-9, sla_window, d_regrow, first_slack_us=min(known, default=float("inf")))
+                          delta_us, 1e-9, sla_window, d_regrow, first_slack_us=min(known, default=float("inf")),
+                          fuse_budget=p.fuse_budget)
         done = np.zeros(self.n, np.int64)
         finish = np.zeros(self.n)
         t, busy, nxt = 0.0, 0.0, 0

@@ -91,7 +91,8 @@ def drive_library(p: AO.AwdParams, arrival, ddl, new_len, service_us, rate_hat=0
     order = sorted(range(n), key=lambda i: (arrival[i], i))
     known = [ddl[i] - t0 - p.s_hat for i in order if arrival[i] <= t0]
     awd = api.LapsAwd(p.len_buckets, p.depths, p.mem_budget, p.sigma, p.w_min, p.w_max, p.s_hat, p.t_max, p.delta,
-                      p.rate_eps, p.sla_window, p.d_regrow, first_slack_us=min(known, default=math.inf))
+                      p.rate_eps, p.sla_window, p.d_regrow, first_slack_us=min(known, default=math.inf),
+                      fuse_budget=p.fuse_budget)
     awd.laps_awd_begin_round(t0)
     done, trace, t = set(), [], t0
     while len(done) < n:
@@ -131,7 +132,7 @@ def test_library_matches_oracle_on_random_workloads(seed):
     p = AO.AwdParams(len_buckets=(16, 32, 64), depths=(1, 2, 4, 8, 16, 32), mem_budget=int(rng.choice([64, 128, 512, 2048])),
                      sigma=float(rng.choice([0.0, 25.0])), w_min=float(rng.choice([0.0, 15.0])), w_max=float(rng.choice([300.0, 2000.0])),
                      s_hat=90.0, t_max=float(rng.choice([math.inf, 700.0])), delta=float(rng.choice([0.0, 10.0])),
-                     sla_window=bool(seed % 2), d_regrow=bool(seed % 3 == 0))
+                     sla_window=bool(seed % 2), d_regrow=bool(seed % 3 == 0), fuse_budget=int(rng.choice([-1, 0, 64, 128])))
     arrival, ddl, new_len = random_workload(rng, 300, with_ddl=seed % 4 != 0)
     svc = lambda lb, d: 70.0 + 0.04 * lb * d
     want = AO.simulate(p, arrival, ddl, new_len, svc, rate_hat=0.02)
