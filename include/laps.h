@@ -275,6 +275,10 @@ int laps_awd_create(const laps_awd_params* p, double first_slack_us, laps_awd** 
 void laps_awd_destroy(laps_awd* awd);
 double laps_awd_window_us(const laps_awd* awd);
 int32_t laps_awd_target_depth(const laps_awd* awd);
+/* Per-shape service-time estimates: s_hat_us is a host array [n_len_buckets][n_depths] (copied); the estimate
+ * used at a decision is then the entry of the captured shape the batch formed at that instant would run in
+ * (NaN entry: the single s_hat_us of the parameters).  NULL removes the table.  EINVAL on a negative entry. */
+int laps_awd_set_service_table(laps_awd* awd, const double* s_hat_us);
 /* The instance is free to form the next short batch from free_at_us on (e.g. when the dispatched step ends).
  * Without this call the next round's timer may start at the dispatch itself.  EINVAL while a round collects. */
 int laps_awd_begin_round(laps_awd* awd, double free_at_us);

@@ -26,7 +26,8 @@ Readings taken where the paper is silent (each also listed with the design notes
   * a batch of mixed buckets runs in the shape of its largest bucket; requests of another bucket than the
     oldest one's join only while the fused shape stays within `fuse_budget` padded tokens (the "graph fusion"
     of Section 3.1 pays only while a step costs one pass over the weights whatever its shape);
-  * r_hat is supplied by the caller (requests per microsecond) for the epoch;
+  * r_hat is supplied by the caller (requests per microsecond) for the epoch; S_hat is one number, or a table
+    per captured shape supplied by the caller (the entry of the shape the current batch would run in);
   * optional growth of D (off in the printed algorithm, where D can only fall): when a round fills its
     target while at least as many requests again are still waiting, D moves to the next larger captured depth
     within the budget.
@@ -118,9 +119,17 @@ class Dispatch:
     tau: float
 
 
-def simulate(p: AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0.0):
+def simulate(p: AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0.0, s_hat_table=None):
     """Runs the short queue alone.  service_us(len_bucket, depth) -> duration of one dispatched step.
+    s_hat_table: optional {(len_bucket, depth): estimate}; the estimate S_hat used at a decision instant is then
+    the entry of the shape the batch formed at that instant would run in (p.s_hat where there is no entry).
     Returns the list of Dispatch records."""
+    def s_hat_of(batch):
+        if not batch or not s_hat_table:
+            return p.s_hat
+        g = nearest_graph(p, max(bucket_of(p, new_len[r]) for r in batch), len(batch))
+        return s_hat_table.get(g, p.s_hat)
+
     n = len(arrival)
     order = sorted(range(n), key=lambda i: (arrival[i], i))
     known = [i for i in order if arrival[i] <= t0]
@@ -139,7 +148,7 @@ def simulate(p: AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0
         if p.sla_window:
             waiting = [i for i in pending if arrival[i] <= t]
             b0, _ = form_batch(p, waiting, new_len, D)
-            w_sla = max(0.0, min(ddl[i] - t - p.s_hat for i in waiting) - p.delta)
+            w_sla = max(0.0, min(ddl[i] - t - s_hat_of(b0) for i in waiting) - p.delta)
             w_gr = max(0, D - len(b0)) / max(rate_hat, p.rate_eps)
             w_round = clip(min(w_sla, w_gr), p.w_min, p.w_max)
         while True:
@@ -147,7 +156,7 @@ def simulate(p: AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0
             batch, nxt = form_batch(p, waiting, new_len, D)
             watch = batch + ([nxt] if nxt is not None else [])
             # the three timed conditions as instants: slack_i <= sigma  <=>  t >= DDL_i - S_hat - sigma, etc.
-            t_sla = min((ddl[i] - p.s_hat - p.sigma for i in watch), default=INF)
+            t_sla = min((ddl[i] - s_hat_of(batch) - p.sigma for i in watch), default=INF)
             t_cap = arrival[waiting[0]] + p.t_max
             t_win = t_start + w_round
             reason = None

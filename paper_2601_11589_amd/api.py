@@ -180,6 +180,7 @@ class LapsAwd:
         prm = _AwdParams(len(lb), lb_p, len(dp), dp_p, int(mem_budget), int(fuse_budget), sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us, delta_us, rate_eps,
                          int(sla_window), int(d_regrow))
         self._h = C.c_void_p()
+        self._grid = (len(lb), len(dp))
         _check(L.laps_awd_create(C.byref(prm), C.c_double(first_slack_us), C.byref(self._h)))
 
     @property
@@ -189,6 +190,15 @@ class LapsAwd:
     @property
     def target_depth(self) -> int:
         return int(lib().laps_awd_target_depth(self._h))
+
+    def laps_awd_set_service_table(self, table):
+        """table: float array [n_len_buckets, n_depths] (NaN = no entry) or None."""
+        if table is None:
+            _check(lib().laps_awd_set_service_table(self._h, None))
+            return
+        t = np.ascontiguousarray(table, dtype=np.float64)
+        assert t.shape == self._grid
+        _check(lib().laps_awd_set_service_table(self._h, t.ctypes.data_as(C.POINTER(C.c_double))))
 
     def laps_awd_begin_round(self, free_at_us: float):
         _check(lib().laps_awd_begin_round(self._h, C.c_double(free_at_us)))

@@ -35,6 +35,7 @@ struct laps_awd {
     bool timer_running;
     double t_start, w_round;
     std::vector<int32_t> bucket_scratch;
+    std::vector<double> s_hat_table;   // [len bucket][depth], NaN = no entry; empty = no table
 };
 
 namespace {
@@ -87,7 +88,37 @@ Batch form_batch(laps_awd* a, int32_t n_waiting, const int32_t* new_len, int32_t
     return b;
 }
 
+// service-time estimate for the batch as it stands: the table entry of its shape, else the default
+double s_hat_of(const laps_awd* a, const Batch& b) {
+    if (b.n == 0 || a->s_hat_table.empty()) return a->s_hat;
+    const int32_t d = nearest_depth(a, b.len_bucket, b.n, a->mem_budget);
+    size_t li = 0, di = 0;
+    while (a->len_buckets[li] != b.len_bucket) ++li;
+    while (a->depths[di] != d) ++di;
+    const double v = a->s_hat_table[li * a->depths.size() + di];
+    return std::isnan(v) ? a->s_hat : v;
+}
+
 }  // namespace
+
+extern "C" int laps_awd_set_service_table(laps_awd* a, const double* s_hat_us) {
+    if (!a) {
+        laps_set_error("awd_set_service_table: NULL handle");
+        return LAPS_EINVAL;
+    }
+    if (!s_hat_us) {
+        a->s_hat_table.clear();
+        return LAPS_OK;
+    }
+    const size_t n = a->len_buckets.size() * a->depths.size();
+    for (size_t i = 0; i < n; ++i)
+        if (s_hat_us[i] < 0.0) {
+            laps_set_error("awd_set_service_table: negative estimate at entry %zu", i);
+            return LAPS_EINVAL;
+        }
+    a->s_hat_table.assign(s_hat_us, s_hat_us + n);
+    return LAPS_OK;
+}
 
 extern "C" int laps_awd_create(const laps_awd_params* p, double first_slack_us, laps_awd** out) {
     if (!p || !out || !p->len_buckets || !p->depths || p->n_len_buckets <= 0 || p->n_depths <= 0) {
@@ -201,15 +232,17 @@ extern "C" int laps_awd_poll(laps_awd* a, double now_us, double rate_hat, int32_
         a->w_round = a->window;
         if (a->sla_window) {
             double slack = kInf;
-            for (int32_t i = 0; i < n_waiting; ++i) slack = std::min(slack, ddl_us[i] - a->t_start - a->s_hat);
+            const double sh = s_hat_of(a, b);
+            for (int32_t i = 0; i < n_waiting; ++i) slack = std::min(slack, ddl_us[i] - a->t_start - sh);
             const double w_sla = std::max(0.0, slack - a->delta);
             const double w_gr = (double)std::max(0, a->target_depth - b.n) / std::max(rate_hat, a->rate_eps);
             a->w_round = clipd(std::min(w_sla, w_gr), a->w_min, a->w_max);
         }
     }
     double t_sla = kInf;
-    for (int32_t j = 0; j < b.n; ++j) t_sla = std::min(t_sla, ddl_us[take_idx[j]] - a->s_hat - a->sigma);
-    if (b.next >= 0) t_sla = std::min(t_sla, ddl_us[b.next] - a->s_hat - a->sigma);
+    const double s_now = s_hat_of(a, b);
+    for (int32_t j = 0; j < b.n; ++j) t_sla = std::min(t_sla, ddl_us[take_idx[j]] - s_now - a->sigma);
+    if (b.next >= 0) t_sla = std::min(t_sla, ddl_us[b.next] - s_now - a->sigma);
     const double t_cap = arrival_us[0] + a->t_max;
     const double t_win = a->t_start + a->w_round;
     int32_t why = LAPS_AWD_NONE;

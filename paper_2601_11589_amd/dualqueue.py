@@ -59,6 +59,7 @@ class DQResult:
         return {"mode": self.mode, "makespan_ms": self.makespan_us / 1e3, "gpu_busy_ms": self.gpu_busy_us / 1e3,
                 "steps": self.n_steps, "step_kinds": self.step_kinds,
                 "tokens_per_s": float(np.sum(new_len)) / (self.makespan_us * 1e-6),
+                "slo_400ms_violation_frac": float(np.mean(self.latency_us > 400_000.0)),
                 "short_latency_ms": {"p50": pc(lat_s, 50), "p90": pc(lat_s, 90), "mean": float(lat_s.mean()) / 1e3},
                 "long_latency_ms": {"p50": pc(lat_l, 50), "p90": pc(lat_l, 90), "mean": float(lat_l.mean()) / 1e3}}
 
@@ -250,6 +251,8 @@ class DualQueue:
         reasons, depths_used = {}, []
         q_s, q_l = [], []
         gap, last_s = None, None
+        # measured replay time per captured shape (exponentially weighted), handed to the library as S_hat
+        s_tab = np.full((len(p.len_buckets), len(p.depths)), np.nan)
         while nxt < self.n or q_s or q_l:
             while nxt < self.n and arrival[order[nxt]] <= t:
                 r = order[nxt]
@@ -278,6 +281,9 @@ class DualQueue:
                     kinds["short_busy_us"] += us
                     reasons[dec["reason"]] = reasons.get(dec["reason"], 0) + 1
                     depths_used.append(len(ids))
+                    li, di = list(p.len_buckets).index(dec["len_bucket"]), list(p.depths).index(dec["depth"])
+                    s_tab[li, di] = us if np.isnan(s_tab[li, di]) else 0.5 * s_tab[li, di] + 0.5 * us
+                    awd.laps_awd_set_service_table(s_tab)
                     for r in ids:
                         done[r] = self.new_len[r]
                         finish[r] = t

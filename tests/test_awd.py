@@ -23,6 +23,11 @@ def params_of(d):
     return AO.AwdParams(**d)
 
 
+def table_of(case):
+    t = case.get("s_hat_table")
+    return {(lb, d): v for lb, d, v in t} if t else None
+
+
 def inf_none(v):
     return [math.inf if x is None else float(x) for x in v]
 
@@ -31,7 +36,7 @@ def inf_none(v):
 def test_oracle_reproduces_hand_worked_traces(case):
     p = params_of(case["params"])
     got = AO.simulate(p, [float(a) for a in case["arrival"]], inf_none(case["ddl"]), case["new_len"],
-                      lambda lb, d: case["service_us"], rate_hat=case["rate_hat"])
+                      lambda lb, d: case["service_us"], rate_hat=case["rate_hat"], s_hat_table=table_of(case))
     assert len(got) == len(case["trace"])
     for g, w in zip(got, case["trace"]):
         assert (g.t, g.req_ids, g.len_bucket, g.depth, g.reason, g.w_after, g.d_after, g.tau) == \
@@ -83,7 +88,7 @@ def test_oracle_all_arrived_deadline_free_is_token_max():
 
 
 # ------------------------------------------------------------------ the library's state machine against the oracle
-def drive_library(p: AO.AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0.0):
+def drive_library(p: AO.AwdParams, arrival, ddl, new_len, service_us, rate_hat=0.0, t0=0.0, s_hat_table=None):
     """Event loop around laps_awd_poll: polls at arrivals, at the returned wake-up times and when the instance
     becomes free; the same clock rules as the oracle's simulation, none of its code."""
     from paper_2601_11589_amd import api
@@ -93,6 +98,11 @@ def drive_library(p: AO.AwdParams, arrival, ddl, new_len, service_us, rate_hat=0
     awd = api.LapsAwd(p.len_buckets, p.depths, p.mem_budget, p.sigma, p.w_min, p.w_max, p.s_hat, p.t_max, p.delta,
                       p.rate_eps, p.sla_window, p.d_regrow, first_slack_us=min(known, default=math.inf),
                       fuse_budget=p.fuse_budget)
+    if s_hat_table is not None:
+        tab = np.full((len(p.len_buckets), len(p.depths)), np.nan)
+        for (lb, d), v in s_hat_table.items():
+            tab[p.len_buckets.index(lb), p.depths.index(d)] = v
+        awd.laps_awd_set_service_table(tab)
     awd.laps_awd_begin_round(t0)
     done, trace, t = set(), [], t0
     while len(done) < n:
@@ -121,7 +131,7 @@ def drive_library(p: AO.AwdParams, arrival, ddl, new_len, service_us, rate_hat=0
 def test_library_reproduces_hand_worked_traces(case):
     p = params_of(case["params"])
     got = drive_library(p, [float(a) for a in case["arrival"]], inf_none(case["ddl"]), case["new_len"],
-                        lambda lb, d: case["service_us"], rate_hat=case["rate_hat"])
+                        lambda lb, d: case["service_us"], rate_hat=case["rate_hat"], s_hat_table=table_of(case))
     want = [(w["t"], w["req_ids"], w["len_bucket"], w["depth"], w["reason"], w["w_after"], w["d_after"]) for w in case["trace"]]
     assert got == want
 
@@ -135,8 +145,11 @@ def test_library_matches_oracle_on_random_workloads(seed):
                      sla_window=bool(seed % 2), d_regrow=bool(seed % 3 == 0), fuse_budget=int(rng.choice([-1, 0, 64, 128])))
     arrival, ddl, new_len = random_workload(rng, 300, with_ddl=seed % 4 != 0)
     svc = lambda lb, d: 70.0 + 0.04 * lb * d
-    want = AO.simulate(p, arrival, ddl, new_len, svc, rate_hat=0.02)
-    got = drive_library(p, arrival, ddl, new_len, svc, rate_hat=0.02)
+    table = None
+    if seed >= 6:       # per-shape estimates: exact for some shapes, absent (default) for the others
+        table = {(lb, d): svc(lb, d) for lb in p.len_buckets for d in p.depths if (lb // 16 + d) % 3}
+    want = AO.simulate(p, arrival, ddl, new_len, svc, rate_hat=0.02, s_hat_table=table)
+    got = drive_library(p, arrival, ddl, new_len, svc, rate_hat=0.02, s_hat_table=table)
     assert len(got) == len(want)
     for g, w in zip(got, want):
         assert g == (w.t, w.req_ids, w.len_bucket, w.depth, w.reason, w.w_after, w.d_after)
