@@ -66,16 +66,20 @@ def build_model(cfg, seed, n_layers=None):
 
 
 # ------------------------------------------------------------------------------------- short buckets
-def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, tag):
+def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, tag, config=2):
     import numpy as np
     import torch
     from paper_2601_11589_amd import api, inputs, runner
 
-    seed = inputs.SEED_BASE + 2
-    b = inputs.make_batch(2)
+    seed = inputs.SEED_BASE + config
+    b = inputs.make_batch(config)
     T = b.n_tokens
     d_x = torch.from_numpy(inputs.make_activations(cfg, seed, T)).cuda()
     k_pools, v_pools = ctx.new_pools(b.n_pages, cfg.n_layers)
+    if int(b.prefix_len.max()) > 0:      # cached prefix content: seeded N(0,1) bf16 drawn on the device
+        gen = torch.Generator(device="cuda").manual_seed(seed)
+        for p in k_pools + v_pools:
+            p.copy_(torch.randn(p.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
     plan_args = (64, LEN_BUCKETS, DEPTHS, token_budget, LONG_CHUNK, b.new_len, b.prefix_len)
     plan = api.laps_plan_buckets(*plan_args)
     assert not plan["longs"]
@@ -155,6 +159,11 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
         res["kernel_launches"] = {k: v[1] for k, v in prof.items()}
         res["gemm"] = {"launches": gcnt, "avg_us": gms / gcnt * 1e3, "bytes_per_launch": gbytes / gcnt,
                        "GBps": gbytes / (gms * 1e-3) / 1e9, "TFLOPs": gflops / (gms * 1e-3) / 1e12}
+        # attention: K and V of every visible position are read once per layer (algorithmic bytes)
+        kv_bytes = float(np.sum(b.new_len + b.prefix_len)) * cfg.n_kv_heads * cfg.head_dim * 2 * 2 * cfg.n_layers
+        ams, acnt = prof["attn"]
+        res["attention"] = {"launches": acnt, "avg_us": ams / max(acnt, 1) * 1e3, "kv_MB_per_launch": kv_bytes / max(acnt, 1) / 1e6,
+                            "kv_GBps": kv_bytes / (ams * 1e-3) / 1e9 if ams > 0 else None}
     sr.close()
     return res
 
@@ -247,6 +256,67 @@ def run_latency_model(layers, cfg):
     res["samples"] = [{k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()} for s in samples]
     ctx.close()
     return res
+
+
+# ------------------------------------------------------------------------------------- graph cost table
+def run_graph_cost(ctx32, layers32):
+    """Capture time, device bytes and replay time of (length, depth) graphs over the paper's example grid
+    (lengths 8..256, depths 1..64, Section 3.1) for 7B-, 14B- and 32B-shaped 4-layer stacks, beside the paper's
+    cost analysis (a few hundred MB and seconds per graph on its stack)."""
+    import numpy as np
+    import torch
+    from paper_2601_11589_amd import api, inputs
+    lens, depths, budget = (8, 16, 32, 64, 128, 256), (1, 2, 4, 8, 16, 32, 64), 4096
+    out = {"grid": {"len_buckets": lens, "depths": depths, "token_budget": budget}, "layers": 4, "models": {}}
+    for name, cfgf in (("7B", inputs.qwen7b_cfg), ("14B", inputs.qwen14b_cfg), ("32B", inputs.qwen32b_cfg)):
+        cfg = cfgf(4)
+        if name == "32B":
+            ctx, layers = ctx32, layers32
+        else:
+            ctx = api.LapsCtx(cfg, max_positions=4096)
+            seed = inputs.SEED_BASE + 60 + len(name)
+            layers = [ctx.upload_layer(inputs.make_layer_weights(cfg, seed, l, threads=min(16, os.cpu_count() or 8)))
+                      for l in range(4)]
+        max_pages = 16          # a 256-token request fills 16 pages
+        k_pools, v_pools = ctx.new_pools(max_pages * 64 + 1, 4, zero=True)
+        stream = torch.cuda.Stream()
+        rows = []
+        for lb in lens:
+            for d in depths:
+                if lb * d > budget:
+                    continue
+                t0 = time.perf_counter()
+                g = ctx.laps_graph_capture(layers, lb, d, max_pages, k_pools, v_pools, stream)
+                stream.synchronize()
+                cap = time.perf_counter() - t0
+                x = torch.zeros((d * lb, cfg.hidden), dtype=torch.float32, device="cuda")
+                sl = torch.full((d,), lb, dtype=torch.int32, device="cuda")
+                pl = torch.zeros(d, dtype=torch.int32, device="cuda")
+                pt = (torch.arange(d * max_pages, dtype=torch.int32, device="cuda") + 1).reshape(d, max_pages).contiguous()
+                g.laps_graph_stage(d, sl, pl, pt, x, stream)
+                g.laps_graph_replay(stream)
+                stream.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(3):
+                    g.laps_graph_replay(stream)
+                e1.record(stream)
+                e1.synchronize()
+                rows.append((lb, d, cap, g.laps_graph_device_bytes(), e0.elapsed_time(e1) / 3))
+                g.close()
+        caps = np.array([r[2] for r in rows])
+        mbs = np.array([r[3] for r in rows]) / 1e6
+        out["models"][name] = {
+            "graphs": len(rows), "capture_s": {"first": float(caps[0]), "median": float(np.median(caps)), "max": float(caps.max())},
+            "device_MB": {"min": float(mbs.min()), "median": float(np.median(mbs)), "max": float(mbs.max()), "sum": float(mbs.sum())},
+            "replay_ms": {f"{lb}x{d}": round(ms, 3) for lb, d, _, _, ms in rows if (lb, d) in ((8, 1), (16, 8), (64, 2), (64, 64), (256, 16))},
+        }
+        del k_pools, v_pools
+        if name != "32B":
+            ctx.close()
+            del layers
+            torch.cuda.empty_cache()
+    return out
 
 
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop
@@ -346,6 +416,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-dual-queue", action="store_true", help="skip the mixed dual-queue workload (configs[4])")
     ap.add_argument("--no-latency-model", action="store_true", help="skip the run-time latency-model fit")
+    ap.add_argument("--no-reprefill", action="store_true", help="skip the multi-turn re-prefill workload (configs[2])")
+    ap.add_argument("--no-graph-cost", action="store_true", help="skip the graph capture cost table (7B/14B/32B shapes)")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
     ap.add_argument("--long-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -405,10 +477,17 @@ def main():
         tm["gemm_TFLOPs"] = gm["TFLOPs"]
         tm["gemm_frac_of_mfma_peak"] = gm["TFLOPs"] / MFMA_BF16_PEAK_TFS
         line["short_token_max"] = tm
+    if not args.no_reprefill:
+        # configs[2]: multi-turn re-prefill, 128 requests of U[16,64] new tokens over U[512,4096] cached tokens
+        rp = run_short(ctx, layers, cfg, args.token_budget, max(2, args.steps // 2), 1, True, "re-prefill", config=3)
+        rp.pop("gemm")
+        line["reprefill"] = rp
     if not args.no_long:
         line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
     if not args.no_latency_model:
         line["latency_model"] = run_latency_model(layers, cfg)
+    if not args.no_graph_cost:
+        line["graph_cost"] = run_graph_cost(ctx, layers)
     if not args.no_dual_queue:
         cfg8 = inputs.qwen32b_cfg(8)
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)

@@ -471,7 +471,9 @@ static constexpr int kSplitTargetBlocks = 512;   // aim for two workgroups per c
 static constexpr int kSplitBelowBlocks = 256;    // launches with fewer un-split workgroups than this are split
 static constexpr int kSplitMax = 64;
 
-size_t laps_attn_partial_bytes(int hd) {
+size_t laps_attn_partial_bytes(int hd, int max_pages) {
+    // page tables too narrow for two splits never take the split path (same test as attn_blocking)
+    if (((long)max_pages * LAPS_PAGE + KT - 1) / KT < 2 * MIN_TILES_PER_SPLIT) return 0;
     // blocks0 < kSplitBelowBlocks and n_split <= ceil(kSplitTargetBlocks / blocks0) give fewer than
     // kSplitTargetBlocks + kSplitBelowBlocks workgroups, each with 128 rows of (hd + 2) floats
     return (size_t)(kSplitTargetBlocks + kSplitBelowBlocks) * 128 * (size_t)(hd + 2) * sizeof(float);

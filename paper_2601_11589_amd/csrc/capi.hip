@@ -51,7 +51,8 @@ static size_t partial_bytes_for(const laps_model_cfg& c, int m) {
     return t > b ? t : b;
 }
 
-static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs) {
+// max_pages: width of the page tables the workspace will serve (default: any width)
+static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs, int max_pages = 1 << 24) {
     WsLayout w;
     const size_t M = (size_t)max_tokens;
     const int qd = c.n_q_heads * c.head_dim;
@@ -79,7 +80,7 @@ static WsLayout ws_layout(const laps_model_cfg& c, int max_tokens, int max_seqs)
         pb = t > pb ? t : pb;
     }
     {   // the same region holds the attention's key-split partial results (the two uses never overlap in time)
-        const size_t t = laps_attn_partial_bytes(c.head_dim);
+        const size_t t = laps_attn_partial_bytes(c.head_dim, max_pages);
         pb = t > pb ? t : pb;
     }
     w.partial = o;    o += align256(pb);
@@ -531,7 +532,7 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
     g->max_pages = max_pages;
     g->n_layers = nl;
     const size_t M = (size_t)len_bucket * depth, d = c->cfg.hidden;
-    const size_t ws_bytes = ws_layout(c->cfg, (int)M, depth).total;
+    const size_t ws_bytes = ws_layout(c->cfg, (int)M, depth, max_pages).total;
     size_t o = 0;
     const size_t o_xin = o;  o += align256(M * d * 4);
     const size_t o_xout = o; o += align256(M * d * 4);

@@ -83,7 +83,7 @@ int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fil
 // `partial` (laps_attn_partial_bytes, 16-byte aligned) receives per-split results when the launch shape
 // calls for splitting the key range; it may be NULL only if max_pages * 16 < 1024.
 // tile_start: n_seq + 1 ints; item_seq: laps_attn_item_table_bytes (sequence of every row-block work item).
-size_t laps_attn_partial_bytes(int hd);
+size_t laps_attn_partial_bytes(int hd, int max_pages);   // 0 when page tables this narrow never split
 size_t laps_attn_item_table_bytes(int max_tokens, int max_seqs, int group);
 int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_pages, int* tile_start, int* item_seq,
                            int n_q, int n_kv, hipStream_t s);

@@ -77,6 +77,16 @@ def qwen32b_cfg(n_layers: int = 4) -> ModelCfg:
     return ModelCfg(5120, 40, 8, 128, 27648, n_layers)
 
 
+def qwen14b_cfg(n_layers: int = 4) -> ModelCfg:
+    """Layer shape of the 14B model of the same family (Numerical Results)."""
+    return ModelCfg(5120, 40, 8, 128, 13824, n_layers)
+
+
+def qwen7b_cfg(n_layers: int = 4) -> ModelCfg:
+    """Layer shape of the 7B model of the same family (Numerical Results): 28 query heads over 4 kv heads."""
+    return ModelCfg(3584, 28, 4, 128, 18944, n_layers)
+
+
 # --------------------------------------------------------------------------- random tensors
 _TENSOR_IDS = {"ln1": 0, "w_qkv": 1, "w_o": 2, "ln2": 3, "w_gate": 4, "w_up": 5, "w_down": 6,
                "x": 7, "lens": 8, "prefix_k": 9, "prefix_v": 10, "pages": 11, "arrivals": 12}

@@ -108,9 +108,9 @@ class SharedCase(Case):
         return self
 
 
-def run_planned_short(case, cfg, ctx, token_budget):
+def run_planned_short(case, cfg, ctx, token_budget, len_buckets=LEN_BUCKETS):
     """Plan -> stage -> replay every short batch as a captured graph; returns y per request."""
-    plan = api.laps_plan_buckets(64, LEN_BUCKETS, DEPTHS, token_budget, 2048, case.new_len, case.prefix_len)
+    plan = api.laps_plan_buckets(len_buckets[-1], len_buckets, DEPTHS, token_budget, 2048, case.new_len, case.prefix_len)
     assert not plan["longs"]
     staged = runner.stage_short_batches(plan, case.new_len, case.prefix_len, case.page_table, case.cu, case.d_x, cfg.hidden)
     stream = torch.cuda.Stream()
@@ -224,6 +224,28 @@ def test_config4_long_prefill_in_chunks(model):
     rel, mx = errors(y[case.cu[i1]:case.cu[i1 + 1]], y_un)
     print(f"[parity] config4 chunked vs unchunked on device ({case.new_len[i1]} tokens): rel_l2={rel:.3e} max_abs={mx:.3e}", flush=True)
     assert rel < 2.0 * floor, (rel, floor)
+
+
+@pytest.mark.parametrize("name,cfgf", [("7B", inputs.qwen7b_cfg), ("14B", inputs.qwen14b_cfg)])
+def test_wider_bucket_grid_on_smaller_model_shapes(name, cfgf):
+    """The length grid the paper gives as an example (8 ... 256, Section 3.1) on the 7B- and 14B-shaped layers it
+    also serves (Numerical Results): every request of a mixed new-prompt / re-prefill set runs in a captured
+    (bucket, depth) graph and is checked against the oracle.  The 7B shape has 7 query heads per kv head."""
+    cfg = cfgf(2)
+    ctx = api.LapsCtx(cfg, max_positions=4096 + 256)
+    seed = inputs.SEED_BASE + 40 + len(name)
+    host_layers = [inputs.make_layer_weights(cfg, seed, l, threads=min(16, os.cpu_count() or 8)) for l in range(2)]
+    dev_layers = [ctx.upload_layer(w) for w in host_layers]
+    rng = np.random.default_rng(seed)
+    new_len = np.array([1, 8, 9, 100, 128, 129, 255, 256, 33, 64, 17, 200], np.int32)
+    prefix_len = np.array([0, 0, 700, 0, 15, 2049, 0, 1, 3000, 16, 0, 640], np.int32)
+    case = SharedCase(cfg, new_len, prefix_len, seed, host_layers, dev_layers).to_device(ctx)
+    ys, plan = run_planned_short(case, cfg, ctx, 512, len_buckets=[8, 16, 32, 64, 128, 256])
+    assert sorted(i for b in plan["batches"] for i in b["req_ids"]) == list(range(case.n))
+    assert {b["len_bucket"] for b in plan["batches"]} == {8, 16, 32, 64, 128, 256}
+    got = np.concatenate([ys[i] for i in range(case.n)])
+    assert_parity(f"{name} shape, buckets 8..256, {len(plan['batches'])} graphs", got, case, None)
+    ctx.close()
 
 
 @pytest.fixture(scope="module")
