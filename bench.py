@@ -319,6 +319,38 @@ def run_graph_cost(ctx32, layers32):
     return out
 
 
+# ------------------------------------------------------------------------------------- spatial mode, simulated
+def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
+    """Algorithm 2 over 8 virtual instances of a full-depth model: queueing and the controller are simulated on the
+    host, every step lasts what it was measured to last on this GPU (4-layer times scaled to `layers_full` layers).
+    short_step_ms_4l: {depth: ms} of one (64-token bucket, depth) replay; long_chunk_ms_4l: ms of one 2048-token chunk."""
+    import numpy as np
+    from paper_2601_11589_amd import poolsim
+    k = layers_full / 4.0
+    depths = sorted(short_step_ms_4l)
+    step = lambda d: 1e3 * k * float(np.interp(d, depths, [short_step_ms_4l[x] for x in depths]))
+    chunk_us = 1e3 * k * long_chunk_ms_4l
+    prm = poolsim.PoolSimParams()
+    # capacities: a SHORT instance serves short_depth requests per step, a LONG one a 5120-token prompt in 2.5 chunks
+    cap_s = prm.short_depth / (step(prm.short_depth) * 1e-6)
+    cap_l = 1.0 / (2.5 * chunk_us * 1e-6)
+    arr, ln, lg = poolsim.shifting_workload(inputs_seed(), 60e6, short_rate_a=0.7 * 5 * cap_s, long_rate_a=0.3 * 3 * cap_l,
+                                            short_rate_b=0.3 * 3 * cap_s, long_rate_b=0.7 * 5 * cap_l)
+    out = {"instances": prm.n_total, "layers": layers_full, "short_step_us_depth8": step(prm.short_depth), "long_chunk_us": chunk_us,
+           "requests": int(len(arr)), "phase_a": "short load 0.7 of 5 instances, long 0.3 of 3",
+           "phase_b": "short load 0.3 of 3 instances, long 0.7 of 5"}
+    for name, ctl in (("static_4_4", False), ("controller", True)):
+        r = poolsim.simulate(arr, ln, lg, step, chunk_us, prm, controller=ctl)
+        r.pop("moves")
+        out[name] = r
+    return out
+
+
+def inputs_seed():
+    from paper_2601_11589_amd import inputs
+    return inputs.SEED_BASE + 6
+
+
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop
 def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
     """configs[4]: 4 long + 512 short / re-prefill requests on an 8-layer stack, Poisson arrivals replayed on a
@@ -488,6 +520,10 @@ def main():
         line["latency_model"] = run_latency_model(layers, cfg)
     if not args.no_graph_cost:
         line["graph_cost"] = run_graph_cost(ctx, layers)
+        if "long_prefill" in line:
+            gc = line["graph_cost"]["models"]["32B"]["replay_ms"]
+            lp = line["long_prefill"]
+            line["pool_sim"] = run_pool_sim({2: gc["64x2"], 64: gc["64x64"]}, lp["ms_per_step"] / lp["n_chunks"])
     if not args.no_dual_queue:
         cfg8 = inputs.qwen32b_cfg(8)
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)

@@ -293,6 +293,29 @@ int laps_awd_poll(laps_awd* awd, double now_us, double rate_hat, int32_t n_waiti
                   const double* ddl_us, const int32_t* new_len, int32_t* action, int32_t* n_take, int32_t* take_idx,
                   int32_t* len_bucket, int32_t* depth, int32_t* reason, double* wake_us);
 
+/* ------------------------------------------------------------------ instance-pressure controller (host)
+ * Algorithm 2 (spatial disaggregation): n_total instances in a SHORT and a LONG pool.  Each control period the
+ * caller passes, per instance of each pool, queue backlog q, SLA deviation e and utilisation u (host arrays);
+ * psi = w_q q + w_e e - w_u u; pool pressure = nearest-rank `quantile` (0.9 in the paper) of its psi values, 0 for
+ * an empty pool.  Outside the cool-down, *action = +1 (one instance LONG -> SHORT) if P_s > (1 + tau) P_l and the
+ * LONG pool holds more than n_min, else -1 (SHORT -> LONG) under the mirrored condition, else 0; the object updates
+ * its pool sizes, the caller chooses which instance moves.  EINVAL if the signal counts disagree with the pools. */
+typedef struct laps_ctrl laps_ctrl;
+typedef struct {
+    int32_t n_total, n_min;
+    double cool_us;  /* no move within this time of the last one */
+    double tau;      /* hysteresis */
+    double w_q, w_e, w_u;
+    double quantile; /* (0, 1] */
+    double min_pressure; /* no move unless the gaining pool's pressure exceeds this; -INFINITY = as printed */
+} laps_ctrl_params;
+int laps_ctrl_create(const laps_ctrl_params* p, int32_t n_short, laps_ctrl** out);
+void laps_ctrl_destroy(laps_ctrl* ctrl);
+int32_t laps_ctrl_n_short(const laps_ctrl* ctrl);
+int laps_ctrl_step(laps_ctrl* ctrl, double now_us, int32_t n_short, const double* q_s, const double* e_s,
+                   const double* u_s, int32_t n_long, const double* q_l, const double* e_l, const double* u_l,
+                   int32_t* action, double* p_short, double* p_long);
+
 const char* laps_last_error(void);
 const char* laps_version(void);
 

@@ -232,6 +232,55 @@ class LapsAwd:
             pass
 
 
+# --------------------------------------------------------------------------- instance-pressure controller
+class _CtrlParams(C.Structure):
+    _fields_ = [("n_total", C.c_int32), ("n_min", C.c_int32), ("cool_us", C.c_double), ("tau", C.c_double),
+                ("w_q", C.c_double), ("w_e", C.c_double), ("w_u", C.c_double), ("quantile", C.c_double),
+                ("min_pressure", C.c_double)]
+
+
+class LapsCtrl:
+    """Handle of the host-side pool controller (laps_ctrl_*): marshalling only."""
+
+    def __init__(self, n_total, n_short, n_min=1, cool_us=0.0, tau=0.1, w_q=1.0, w_e=1.0, w_u=1.0, quantile=0.9,
+                 min_pressure=float("-inf")):
+        L = lib()
+        L.laps_ctrl_destroy.restype = None
+        L.laps_ctrl_destroy.argtypes = [C.c_void_p]
+        L.laps_ctrl_n_short.argtypes = [C.c_void_p]
+        prm = _CtrlParams(n_total, n_min, cool_us, tau, w_q, w_e, w_u, quantile, min_pressure)
+        self._h = C.c_void_p()
+        self.n_total = n_total
+        _check(L.laps_ctrl_create(C.byref(prm), C.c_int32(n_short), C.byref(self._h)))
+
+    @property
+    def n_short(self) -> int:
+        return int(lib().laps_ctrl_n_short(self._h))
+
+    def laps_ctrl_step(self, now_us, short_signals, long_signals):
+        """signals: sequences of (q, e, u) per instance.  Returns (action, P_s, P_l)."""
+        def cols(sig):
+            a = np.ascontiguousarray(np.asarray(sig, np.float64).reshape(-1, 3).T)
+            return a, [a[i].ctypes.data_as(C.POINTER(C.c_double)) for i in range(3)]
+        a_s, p_s = cols(short_signals)
+        a_l, p_l = cols(long_signals)
+        action, ps, pl = C.c_int32(), C.c_double(), C.c_double()
+        _check(lib().laps_ctrl_step(self._h, C.c_double(now_us), C.c_int32(a_s.shape[1]), *p_s, C.c_int32(a_l.shape[1]),
+                                    *p_l, C.byref(action), C.byref(ps), C.byref(pl)))
+        return action.value, ps.value, pl.value
+
+    def close(self):
+        if self._h:
+            lib().laps_ctrl_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 # --------------------------------------------------------------------------- context
 def bf16_tensor(bits: np.ndarray, device="cuda") -> torch.Tensor:
     """uint16 bf16 bit patterns (host) -> torch.bfloat16 tensor on the device."""
