@@ -343,18 +343,26 @@ GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
     if (m <= 128) {
         // Bandwidth-bound.  The L2 -> CU path carries W once plus the A slab once per workgroup per
         // K step, and saturates near 9 TB/s in aggregate: a 256-column tile halves the A share of a
-        // 128-column one.  One workgroup (8 waves) per CU; K is split only to reach ~256 workgroups,
-        // since every extra slice writes and re-reads m*n fp32 partial sums.
-        int cfg = 5;
-        if (n % 256 != 0) cfg = (n % 128 == 0) ? 0 : 1;
+        // 128-column one, which decides the wide projections (gate/up: 5.3 against 4.4 TB/s).  A narrow
+        // projection (q/k/v, o: 20-28 tiles of 256 columns) never gets near that limit; it pays for the
+        // K split that has to fill the chip - every slice writes m*n fp32 partial sums that a reduce
+        // kernel reads back - and for the short pipeline of each slice.  128-column tiles need half the
+        // split; they win where the 256-column slices would be shorter than 24 K slabs (measured with
+        // cold weights at m = 128: q/k/v 33.8 -> 26.7 us, o 29.0 -> 22.4, 7B-shaped down 43.8 -> 37.4;
+        // the 32B down projection, 36 slabs per slice, is even and stays on 256 columns).  At most 256
+        // workgroups either way: a streaming kernel with 257 leaves one CU with twice the work.
+        auto auto_split = [&](int c) {
+            const int min_steps = c == 5 ? 8 : 16;   // K slabs per slice below which the pipeline is all prologue
+            int sp = 256 / (n / kTiles[c].bn);
+            const int cap = (ksteps + min_steps / 2) / min_steps;
+            sp = sp > cap ? cap : sp;
+            return sp < 1 ? 1 : sp;
+        };
+        int cfg;
+        if (n % 256 == 0 && (n % 128 != 0 || ksteps / auto_split(5) >= 24)) cfg = 5;
+        else cfg = (n % 128 == 0) ? 0 : 1;
         if (cfg == 1 && want_epi == EPI_SWIGLU) want_epi = EPI_PARTIAL;
-        const int tiles = n / kTiles[cfg].bn;
-        int split = force_split;
-        if (split <= 0) {
-            split = 256 / tiles;
-            const int cap = ksteps / 8 > 1 ? ksteps / 8 : 1;
-            if (split > cap) split = cap;
-        }
+        const int split = force_split > 0 ? force_split : auto_split(cfg);
         return finish(cfg, split);
     }
     // compute-bound: minimise rounds(tiles*split over 256 CUs) * per-workgroup MFMA time + the
