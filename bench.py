@@ -487,7 +487,7 @@ def main():
     g = short.pop("gemm")
     # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
     # plain copy of known size (profiles/short_bucket_gemm_hbm_traffic.md); valid for the default token budget
-    traffic = 286.1e6 if args.token_budget == 128 else None
+    traffic = 273.1e6 if args.token_budget == 128 else None
     line = {
         "metric": METRIC, "value": short["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": short["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -497,7 +497,7 @@ def main():
                    "layers": cfg.n_layers, "requests": 256, "token_budget": args.token_budget},
         "latency_ms": {"p50": short["latency_ms_p50"], "p90": short["latency_ms_p90"],
                        "what": "per request: stage+replay time of the bucket batch that serves it"},
-        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<128,256,2,4,*,2> (all four projections of every layer)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<128,256,2,4,*,2> (gate/up, down) and gemm_kernel<128,128,2,2,0,2> (q/k/v, o): all four projections of every layer",
                      "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g["GBps"] / HBM_PEAK_GBS,
                      "traffic": traffic, "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"],
                      "launches": g["launches"], "TFLOPs": g["TFLOPs"]},
