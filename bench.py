@@ -325,7 +325,7 @@ def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
     host, every step lasts what it was measured to last on this GPU (4-layer times scaled to `layers_full` layers).
     short_step_ms_4l: {depth: ms} of one (64-token bucket, depth) replay; long_chunk_ms_4l: ms of one 2048-token chunk."""
     import numpy as np
-    from paper_2601_11589_amd import poolsim
+    from paper_2601_11589_amd import inputs, poolsim
     k = layers_full / 4.0
     depths = sorted(short_step_ms_4l)
     step = lambda d: 1e3 * k * float(np.interp(d, depths, [short_step_ms_4l[x] for x in depths]))
@@ -334,7 +334,7 @@ def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
     # capacities: a SHORT instance serves short_depth requests per step, a LONG one a 5120-token prompt in 2.5 chunks
     cap_s = prm.short_depth / (step(prm.short_depth) * 1e-6)
     cap_l = 1.0 / (2.5 * chunk_us * 1e-6)
-    arr, ln, lg = poolsim.shifting_workload(inputs_seed(), 60e6, short_rate_a=0.7 * 5 * cap_s, long_rate_a=0.3 * 3 * cap_l,
+    arr, ln, lg = poolsim.shifting_workload(inputs.SEED_BASE + 6, 60e6, short_rate_a=0.7 * 5 * cap_s, long_rate_a=0.3 * 3 * cap_l,
                                             short_rate_b=0.3 * 3 * cap_s, long_rate_b=0.7 * 5 * cap_l)
     out = {"instances": prm.n_total, "layers": layers_full, "short_step_us_depth8": step(prm.short_depth), "long_chunk_us": chunk_us,
            "requests": int(len(arr)), "phase_a": "short load 0.7 of 5 instances, long 0.3 of 3",
@@ -344,11 +344,6 @@ def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
         r.pop("moves")
         out[name] = r
     return out
-
-
-def inputs_seed():
-    from paper_2601_11589_amd import inputs
-    return inputs.SEED_BASE + 6
 
 
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop

@@ -67,6 +67,16 @@ def lib():
         L.laps_lm_boundary_prefill.argtypes = [C.c_double] * 3
         L.laps_lm_boundary_reprefill.restype = C.c_double
         L.laps_lm_boundary_reprefill.argtypes = [C.c_double] * 5
+        L.laps_awd_window_us.restype = C.c_double
+        L.laps_awd_window_us.argtypes = [C.c_void_p]
+        L.laps_awd_target_depth.restype = C.c_int32
+        L.laps_awd_target_depth.argtypes = [C.c_void_p]
+        L.laps_awd_destroy.restype = None
+        L.laps_awd_destroy.argtypes = [C.c_void_p]
+        L.laps_awd_begin_round.argtypes = [C.c_void_p, C.c_double]
+        L.laps_ctrl_destroy.restype = None
+        L.laps_ctrl_destroy.argtypes = [C.c_void_p]
+        L.laps_ctrl_n_short.argtypes = [C.c_void_p]
         L.laps_plan_free.argtypes = [C.c_void_p]
         L.laps_ctx_destroy.argtypes = [C.c_void_p]
         L.laps_graph_destroy.argtypes = [C.c_void_p]
@@ -169,13 +179,6 @@ class LapsAwd:
                  t_max_us=float("inf"), delta_us=0.0, rate_eps=1e-9, sla_window=False, d_regrow=False,
                  first_slack_us=float("inf"), fuse_budget=-1):
         L = lib()
-        L.laps_awd_window_us.restype = C.c_double
-        L.laps_awd_window_us.argtypes = [C.c_void_p]
-        L.laps_awd_target_depth.restype = C.c_int32
-        L.laps_awd_target_depth.argtypes = [C.c_void_p]
-        L.laps_awd_destroy.restype = None
-        L.laps_awd_destroy.argtypes = [C.c_void_p]
-        L.laps_awd_begin_round.argtypes = [C.c_void_p, C.c_double]
         (lb, lb_p), (dp, dp_p) = _i32(len_buckets), _i32(depths)
         prm = _AwdParams(len(lb), lb_p, len(dp), dp_p, int(mem_budget), int(fuse_budget), sigma_us, w_min_us, w_max_us, s_hat_us, t_max_us, delta_us, rate_eps,
                          int(sla_window), int(d_regrow))
@@ -245,9 +248,6 @@ class LapsCtrl:
     def __init__(self, n_total, n_short, n_min=1, cool_us=0.0, tau=0.1, w_q=1.0, w_e=1.0, w_u=1.0, quantile=0.9,
                  min_pressure=float("-inf")):
         L = lib()
-        L.laps_ctrl_destroy.restype = None
-        L.laps_ctrl_destroy.argtypes = [C.c_void_p]
-        L.laps_ctrl_n_short.argtypes = [C.c_void_p]
         prm = _CtrlParams(n_total, n_min, cool_us, tau, w_q, w_e, w_u, quantile, min_pressure)
         self._h = C.c_void_p()
         self.n_total = n_total

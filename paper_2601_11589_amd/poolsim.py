@@ -98,8 +98,7 @@ def simulate(arrival_us, new_len, is_long, short_step_us, long_chunk_us, p: Pool
                     fin = [d for e, d in devs[k] if e <= t]
                     out.append((queue_len / max(len(ids), 1), float(np.mean(fin)) if fin else 0.0, busy / p.period_us))
                 return out
-            sig = signals
-            action, ps, pl = ctrl.laps_ctrl_step(t, sig(ids_s, len(q_s)), sig(ids_l, len(q_l)))
+            action, ps, pl = ctrl.laps_ctrl_step(t, signals(ids_s, len(q_s)), signals(ids_l, len(q_l)))
             if action != 0:
                 donors = ids_l if action > 0 else ids_s
                 k = min(donors, key=lambda j: free_at[j])
