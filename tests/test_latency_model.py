@@ -56,3 +56,30 @@ def test_library_fit_matches_lstsq_and_recovers_planted_coefficients():
         api.laps_lm_fit(L, 2 * L, tc, tm)            # H proportional to L: gamma_w and gamma_r not separable
     with pytest.raises(api.LapsError):
         api.laps_lm_fit(L[:1], H[:1], tc[:1], tm[:1])
+
+
+def test_fit_and_boundaries_on_planted_samples():
+    """The sample post-processing (no GPU needed): planted coefficients come back, the reported boundaries are the
+    oracle's roots, and the knee with a constant weight-streaming floor solves its own balance equation."""
+    from paper_2601_11589_amd import inputs, latency_fit
+    cfg = inputs.qwen32b_cfg(4)
+    a, b, gw, gr, floor = 6e-5, 3.7, 0.03, 0.017, 740.0
+    samples = []
+    for H in (0, 1024, 4096, 16384):
+        for L in (16, 32, 64, 128, 256, 512, 1024, 2048):
+            gemm, attn = max(floor, b * L), a * L * (L + 2 * H)
+            samples.append(dict(L=L, H=H, t_comp_us=gemm + attn, gemm_us=gemm, attn_us=attn, t_mem_us=gw * L + gr * H,
+                                kv_write_us=gw * L, kv_read_us=gr * H, stack_us=gemm + attn))
+    r = latency_fit.fit_and_boundaries(samples, cfg, 4)
+    assert (r["alpha"], r["beta"], r["gamma_w"], r["gamma_r"]) == pytest.approx((a, b, gw, gr), rel=2e-3)
+    assert r["L_m_prefill"] == LO.boundary(r["alpha"], r["beta"], r["gamma_w"], r["gamma_r"], 0.0) == 0.0
+    for h, v in r["L_m_reprefill"].items():
+        assert v == pytest.approx(LO.boundary(r["alpha"], r["beta"], r["gamma_w"], r["gamma_r"], float(h)), rel=1e-9)
+    assert r["L_m_reprefill_limit"] == pytest.approx(gr / (2 * a), rel=5e-3)
+    assert r["weight_floor_us"] == floor
+    for h, knee in r["knee_with_weight_floor"].items():
+        H = float(h)
+        comp = r["alpha"] * knee * (knee + 2 * H) + r["beta"] * knee
+        mem = r["gamma_w"] * knee + r["gamma_r"] * H + floor
+        assert comp == pytest.approx(mem, rel=1e-9)
+    assert 150 < r["knee_with_weight_floor"]["0"] < 250
