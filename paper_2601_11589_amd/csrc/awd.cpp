@@ -93,8 +93,9 @@ double s_hat_of(const laps_awd* a, const Batch& b) {
     if (b.n == 0 || a->s_hat_table.empty()) return a->s_hat;
     const int32_t d = nearest_depth(a, b.len_bucket, b.n, a->mem_budget);
     size_t li = 0, di = 0;
-    while (a->len_buckets[li] != b.len_bucket) ++li;
-    while (a->depths[di] != d) ++di;
+    while (li < a->len_buckets.size() && a->len_buckets[li] != b.len_bucket) ++li;
+    while (di < a->depths.size() && a->depths[di] != d) ++di;
+    if (li == a->len_buckets.size() || di == a->depths.size()) return a->s_hat;   // no captured shape: default
     const double v = a->s_hat_table[li * a->depths.size() + di];
     return std::isnan(v) ? a->s_hat : v;
 }

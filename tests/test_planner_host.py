@@ -109,3 +109,18 @@ def test_planner_under_address_and_ub_sanitizers(repo_root, tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
     run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
     assert run.returncode == 0 and run.stdout.strip().endswith("OK"), (run.stdout[-500:], run.stderr[-2000:])
+
+
+def test_host_objects_under_address_and_ub_sanitizers(repo_root, tmp_path):
+    """Host code only: the AWD state machine, the pool controller and the latency-model helpers, driven by seeded
+    random event loops, built with -fsanitize=address,undefined."""
+    exe = str(tmp_path / "host_san")
+    csrc = os.path.join(repo_root, "paper_2601_11589_amd", "csrc")
+    src = [os.path.join(csrc, f) for f in ("awd.cpp", "pool_ctrl.cpp", "latency_model.cpp")] + \
+          [os.path.join(repo_root, "tests", "host_objects_sanitize_driver.cpp")]
+    build = subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                            "-o", exe] + src, capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=180)
+    assert run.returncode == 0 and run.stdout.strip().endswith("OK"), (run.stdout[-500:], run.stderr[-2000:])
