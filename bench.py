@@ -27,8 +27,11 @@ DEPTHS = [1, 2, 4, 8, 16, 32, 64]
 LONG_CHUNK = 2048
 
 
+_T0 = time.perf_counter()
+
+
 def log(*a):
-    print(*a, file=sys.stderr, flush=True)
+    print(f"[{time.perf_counter() - _T0:6.1f}s]", *a, file=sys.stderr, flush=True)
 
 
 def pct(v, q):
@@ -144,15 +147,36 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
         torch.cuda.synchronize()
         gbytes = 0.0
         gflops = 0.0
+        prof = {}
+        per_shape = {}
         with torch.cuda.stream(stream):
-            for (cu, sl, pl, pt, x, M) in padded:
+            for sb, (cu, sl, pl, pt, x, M) in zip(staged, padded):
+                ctx.laps_prof_enable(True)            # (re)starts the per-class timers: one read per batch
                 ctx.laps_prefill_stack(layers, cu, sl, pl, pt, k_pools, v_pools, x, None, stream)
+                stream.synchronize()
+                one = ctx.laps_prof_read()
+                for k, v in one.items():
+                    acc = prof.setdefault(k, [0.0, 0])
+                    acc[0] += v[0]
+                    acc[1] += v[1]
+                by, fl = 0.0, 0.0
                 for (n, kk) in gemm_shapes(cfg).values():
-                    gbytes += cfg.n_layers * (n * kk * 2 + M * kk * 2 + M * n * 4)
-                    gflops += cfg.n_layers * 2.0 * M * n * kk
-        stream.synchronize()
-        prof = ctx.laps_prof_read()
+                    by += cfg.n_layers * (n * kk * 2 + M * kk * 2 + M * n * 4)
+                    fl += cfg.n_layers * 2.0 * M * n * kk
+                gbytes += by
+                gflops += fl
+                ps = per_shape.setdefault(f"{sb.len_bucket}x{sb.depth}", [0.0, 0.0, 0.0, 0])
+                ps[0] += sum(one[k][0] for k in gemm_shapes(cfg))
+                ps[1] += by
+                ps[2] += fl
+                ps[3] += 1
         ctx.laps_prof_enable(False)
+        prof = {k: (v[0], v[1]) for k, v in prof.items()}
+        # both roofline fractions of the four projections for every captured shape
+        res["gemm_per_shape"] = {k: {"batches": v[3], "rows": int(k.split("x")[0]) * int(k.split("x")[1]),
+                                     "hbm_frac": v[1] / (v[0] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                     "mfma_frac": v[2] / (v[0] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFS}
+                                 for k, v in per_shape.items()}
         gms = sum(prof[k][0] for k in gemm_shapes(cfg))
         gcnt = sum(prof[k][1] for k in gemm_shapes(cfg))
         res["kernel_ms"] = {k: round(v[0], 4) for k, v in prof.items()}
@@ -347,7 +371,7 @@ def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
 
 
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop
-def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
+def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,)):
     """configs[4]: 4 long + 512 short / re-prefill requests on an 8-layer stack, Poisson arrivals replayed on a
     virtual clock that advances by measured GPU step time.  Unified FCFS mixed batches vs temporal disaggregation."""
     import numpy as np
@@ -369,32 +393,40 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, load=0.7):
     dq.run_unified(zeros)
     u0 = dq.run_unified(zeros)
     d0 = dq.run_disaggregated(zeros, 0.0)
+    # algorithmic flops of the whole workload: projections on real tokens + causal attention over prefix and new tokens
+    total_flops = (2.0 * cfg8.params_per_layer * b.n_tokens + float(attn_flops(cfg8, b.new_len, b.prefix_len))) * cfg8.n_layers
+
+    def summ(r, extra=None):
+        sm = r.summary(b.new_len, is_long)
+        sm["mfma_frac_of_peak_while_busy"] = total_flops / (r.gpu_busy_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFS
+        if extra:
+            sm.update(extra)
+        return sm
+
     res = {"requests": int(b.n), "real_tokens": int(b.n_tokens), "layers": cfg8.n_layers,
-           "back_to_back": {"unified": u0.summary(b.new_len, is_long), "disaggregated": d0.summary(b.new_len, is_long)},
-           "load": load, "poisson": []}
-    rate = load * b.n / (u0.makespan_us * 1e-6)
-    arr = inputs.poisson_arrivals_us(seed, b.n, rate).astype(np.float64)
-    # long requests are spread uniformly over the arrival horizon
-    horizon = float(arr.max())
-    longs = np.nonzero(is_long)[0]
-    for j, i in enumerate(longs):
-        arr[i] = horizon * j / len(longs)
-    res["arrival_rate_per_s"] = rate
-    res["poisson"].append(dq.run_unified(arr).summary(b.new_len, is_long))
-    for w in windows_us:
-        res["poisson"].append(dq.run_disaggregated(arr, float(w)).summary(b.new_len, is_long))
-    # Adaptive-Wait-Depth batching of the short queue (Algorithm 1): deadline-free, then with a 50 ms TTFT deadline
+           "algorithmic_TFLOP": total_flops / 1e12,
+           "back_to_back": {"unified": summ(u0), "disaggregated": summ(d0)}, "poisson": []}
     s_hat = d0.step_kinds["short_busy_us"] / max(d0.step_kinds["short_graph"], 1)   # mean short step, measured
     dq.run_awd(zeros)                          # warm-up: captures the fused shapes AWD dispatches
-    res["back_to_back"]["awd"] = dq.run_awd(zeros, s_hat_us=s_hat).summary(b.new_len, is_long)
-    res["poisson"].append(dq.run_awd(arr, s_hat_us=s_hat, w_max_us=10_000.0).summary(b.new_len, is_long))
-    ddl = arr + 50_000.0
-    for sla_window in (False, True):
+    res["back_to_back"]["awd"] = summ(dq.run_awd(zeros, s_hat_us=s_hat))
+    longs = np.nonzero(is_long)[0]
+    for ld in loads:
+        log(f"[bench:dual-queue] load {ld}")
+        rate = ld * b.n / (u0.makespan_us * 1e-6)
+        arr = inputs.poisson_arrivals_us(seed, b.n, rate).astype(np.float64)
+        horizon = float(arr.max())
+        for j, i in enumerate(longs):        # long requests are spread uniformly over the arrival horizon
+            arr[i] = horizon * j / len(longs)
+        tag = {"load": ld, "arrival_rate_per_s": rate}
+        res["poisson"].append(summ(dq.run_unified(arr), tag))
+        for w in (windows_us if ld == loads[len(loads) // 2] else windows_us[1:2]):   # full window sweep at the middle load
+            res["poisson"].append(summ(dq.run_disaggregated(arr, float(w)), tag))
+        # Adaptive-Wait-Depth batching of the short queue (Algorithm 1): deadline-free, then with a 50 ms TTFT deadline
+        res["poisson"].append(summ(dq.run_awd(arr, s_hat_us=s_hat, w_max_us=10_000.0), tag))
+        ddl = arr + 50_000.0
         r = dq.run_awd(arr, ddl_us=ddl, s_hat_us=s_hat, sigma_us=2_000.0, w_max_us=10_000.0, t_max_us=25_000.0,
-                       delta_us=1_000.0, sla_window=sla_window)
-        sm = r.summary(b.new_len, is_long)
-        sm["short_deadline_50ms_met_frac"] = float(np.mean(r.latency_us[~is_long] <= 50_000.0))
-        res["poisson"].append(sm)
+                       delta_us=1_000.0, sla_window=True)
+        res["poisson"].append(summ(r, dict(tag, short_deadline_50ms_met_frac=float(np.mean(r.latency_us[~is_long] <= 50_000.0)))))
     dq.close()
     del k_pools, v_pools
     return res
@@ -446,6 +478,8 @@ def main():
     ap.add_argument("--no-reprefill", action="store_true", help="skip the multi-turn re-prefill workload (configs[2])")
     ap.add_argument("--no-graph-cost", action="store_true", help="skip the graph capture cost table (7B/14B/32B shapes)")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
+    ap.add_argument("--loads", type=str, default="0.7",
+                    help="dual queue: Poisson arrival rates as fractions of the unified back-to-back service rate")
     ap.add_argument("--long-steps", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -478,6 +512,7 @@ def main():
     ctx, layers_all, host_layers = build_model(cfg, inputs.SEED_BASE + 2, n_build)
     layers = layers_all[:4]
 
+    log("[bench] leg: short buckets (configs[1])")
     short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short")
     g = short.pop("gemm")
     # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
@@ -499,6 +534,7 @@ def main():
         "short": short,
     }
     if not args.no_token_max:
+        log("[bench] leg: short buckets, token-max")
         tm = run_short(ctx, layers, cfg, 4096, max(2, args.steps // 2), 1, True, "token-max")
         gm = tm.pop("gemm")
         tm["gemm_TFLOPs"] = gm["TFLOPs"]
@@ -506,14 +542,18 @@ def main():
         line["short_token_max"] = tm
     if not args.no_reprefill:
         # configs[2]: multi-turn re-prefill, 128 requests of U[16,64] new tokens over U[512,4096] cached tokens
+        log("[bench] leg: re-prefill (configs[2])")
         rp = run_short(ctx, layers, cfg, args.token_budget, max(2, args.steps // 2), 1, True, "re-prefill", config=3)
         rp.pop("gemm")
         line["reprefill"] = rp
     if not args.no_long:
+        log("[bench] leg: long prefill (configs[3])")
         line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
     if not args.no_latency_model:
+        log("[bench] leg: latency model fit")
         line["latency_model"] = run_latency_model(layers, cfg)
     if not args.no_graph_cost:
+        log("[bench] leg: graph cost table")
         line["graph_cost"] = run_graph_cost(ctx, layers)
         if "long_prefill" in line:
             gc = line["graph_cost"]["models"]["32B"]["replay_ms"]
@@ -521,10 +561,13 @@ def main():
             line["pool_sim"] = run_pool_sim({2: gc["64x2"], 64: gc["64x64"]}, lp["ms_per_step"] / lp["n_chunks"])
     if not args.no_dual_queue:
         cfg8 = inputs.qwen32b_cfg(8)
+        log("[bench] leg: dual queue (configs[4])")
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)
-        line["dual_queue"] = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")])
+        line["dual_queue"] = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")],
+                                            tuple(float(x) for x in args.loads.split(",")))
         ctx8.close()
     if not args.no_cpu:
+        log("[bench] leg: oracle on host cores")
         line["cpu_baseline"] = cpu_baseline(cfg, host_layers[:4], n_sample_req=64)
     else:
         line["cpu_baseline"] = None
