@@ -486,7 +486,7 @@ def main():
                          "readings of the same run can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (replicas are independent; see DESIGN.md); "
+        print("bench.py: this build measures one GPU only (replicas are independent copies of the whole model); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -17,7 +17,7 @@ SLA-constrained and deadline-free modes):
   * SLA-constrained mode (Section 3.2a) takes, at the start of a decision epoch,
     W = clip(min(W_SLA, W_GR), [W_min, W_max]) with W_SLA = max(0, min_{i in Q_s}(DDL_i - t - S_hat) - delta)
     and W_GR = max(0, D - depth(B)) / max(r_hat, eps).
-Readings taken where the paper is silent (each also listed with the design notes of this build):
+Readings taken where the paper is silent:
   * one request's memory is its padded length bucket; mem(G) = L_b(G) * depth(G) padded tokens;
   * the timer of a round starts when the instance is free AND a short request is waiting;
   * "bucket-first": among waiting requests (arrival order), those in the length bucket of the oldest one
