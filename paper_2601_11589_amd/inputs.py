@@ -89,7 +89,7 @@ def qwen7b_cfg(n_layers: int = 4) -> ModelCfg:
 
 # --------------------------------------------------------------------------- random tensors
 _TENSOR_IDS = {"ln1": 0, "w_qkv": 1, "w_o": 2, "ln2": 3, "w_gate": 4, "w_up": 5, "w_down": 6,
-               "x": 7, "lens": 8, "prefix_k": 9, "prefix_v": 10, "pages": 11, "arrivals": 12}
+               "x": 7, "lens": 8, "prefix_k": 9, "prefix_v": 10, "pages": 11, "arrivals": 12, "b_qkv": 13}
 
 
 def _rng(seed: int, layer: int, name: str, extra: int = 0) -> np.random.Generator:
@@ -124,6 +124,12 @@ def make_layer_weights(cfg: ModelCfg, seed: int, layer: int, threads: int = 8) -
 
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return dict(ex.map(one, shapes.keys()))
+
+
+def make_qkv_bias(cfg: ModelCfg, seed: int, layer: int) -> np.ndarray:
+    """bf16 bit pattern of a q/k/v projection bias, [qkv_dim], N(0, 0.5^2) (the model family the paper serves has one;
+    the benchmark configurations leave it off)."""
+    return _normal_bf16(seed, layer, "b_qkv", (cfg.qkv_dim,), 0.5)
 
 
 def make_activations(cfg: ModelCfg, seed: int, n_tokens: int) -> np.ndarray:

@@ -40,7 +40,7 @@ def errors(got: np.ndarray, want: np.ndarray):
 class Case:
     """One ragged batch with weights, activations and cached prefix KV, all seeded."""
 
-    def __init__(self, cfg, new_len, prefix_len, seed, n_layers=None, spare_pages=3):
+    def __init__(self, cfg, new_len, prefix_len, seed, n_layers=None, spare_pages=3, qkv_bias=False):
         self.cfg = cfg
         self.n_layers = n_layers or cfg.n_layers
         self.new_len = np.asarray(new_len, np.int32)
@@ -51,6 +51,9 @@ class Case:
         self.T = int(self.cu[-1])
         self.page_table, self.n_pages = inputs.make_page_table(seed, self.new_len, self.prefix_len, spare_pages)
         self.host_layers = [inputs.make_layer_weights(cfg, seed, l) for l in range(self.n_layers)]
+        if qkv_bias:
+            for l, w in enumerate(self.host_layers):
+                w["b_qkv"] = inputs.make_qkv_bias(cfg, seed, l)
         self.x = inputs.make_activations(cfg, seed, self.T)
         # prefix KV bits: [layer][seq] -> (k, v) or None
         self.prefix = [[inputs.make_prefix_kv(cfg, seed, l, i, int(h)) if h > 0 else None

@@ -177,6 +177,30 @@ def test_tiny_stack_with_prefix_and_ragged_tail():
     ctx.close()
 
 
+def test_tiny_stack_with_qkv_bias():
+    """The q/k/v projection bias of the model family the paper serves (off in the benchmark configurations):
+    a small batch (skinny GEMM path) and a 300-row one (wide tiles), with prefixes, against the oracle; the
+    appended keys and values carry the bias too.  A context created without the flag rejects nothing but ignores
+    the bias, so the two outputs must differ."""
+    cfg = inputs.tiny_cfg(2)
+    for lens, pres in (([7, 33, 1], [0, 20, 130]), ([200, 64, 36], [0, 17, 0])):
+        case = Case(cfg, lens, pres, 909, qkv_bias=True)
+        ctx = api.LapsCtx(cfg, max_positions=512, has_qkv_bias=True)
+        case.to_device(ctx)
+        y_gpu = case.run_stack()
+        _, ks, vs = check_stack(case, y_gpu, "tiny stack with qkv bias")
+        k_gpu, v_gpu = case.gathered_new_kv(1)
+        k_want = np.concatenate(ks[1])
+        v_want = np.concatenate(vs[1])
+        assert errors(k_gpu, k_want)[0] < 6e-3 and errors(v_gpu, v_want)[0] < 6e-3
+        ctx.close()
+        ctx0 = api.LapsCtx(cfg, max_positions=512, has_qkv_bias=False)
+        case.to_device(ctx0)
+        y_nobias = case.run_stack()
+        assert errors(y_nobias, y_gpu)[0] > 1e-2
+        ctx0.close()
+
+
 def test_cached_prefix_equals_full_prefill_on_device():
     """prefill(prefix || new) == prefill(prefix) followed by re-prefill(new) over the cache written by the first."""
     cfg = inputs.tiny_cfg(2)

@@ -275,3 +275,28 @@ def test_storage_rounding_variant_is_close_to_exact():
     y1, _, _ = O.layer_forward(cfg, w, x, [4, 6], None, None, storage_rounding=True)
     rel = np.linalg.norm(y1 - y0) / np.linalg.norm(y0)
     assert 0 < rel < 5e-3
+
+
+def test_qkv_bias_closed_form():
+    """With a zero q/k/v matrix every token's q, k, v is the bias itself: all value rows of a kv head are equal,
+    so attention returns that row whatever the probabilities, and with a zero down projection the layer output is
+    x + W_o a, where a repeats the value bias of each kv head over its group of query heads.  Catches a bias that
+    is dropped, added to the wrong segment, or a wrong head-to-group mapping."""
+    cfg = cfg_of(32, 6, 2, 8, 48)
+    rng = np.random.default_rng(5)
+    w = rand_weights(cfg, rng)
+    w["w_qkv"] = np.zeros_like(w["w_qkv"])
+    w["w_down"] = np.zeros_like(w["w_down"])
+    q_dim, kv_dim = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    w["b_qkv"] = rng.standard_normal(q_dim + 2 * kv_dim)
+    new_len = [3, 7]
+    x = rng.standard_normal((10, cfg.hidden))
+    y, new_k, new_v = O.layer_forward(cfg, w, x, new_len, [None, None], [None, None])[:3]
+    hd, G = cfg.head_dim, cfg.n_q_heads // cfg.n_kv_heads
+    b_v = w["b_qkv"][q_dim + kv_dim:].reshape(cfg.n_kv_heads, hd)
+    a = np.concatenate([b_v[h // G] for h in range(cfg.n_q_heads)])
+    assert np.allclose(y, x + w["w_o"] @ a, rtol=0, atol=1e-12)
+    for i, L in enumerate(new_len):
+        assert np.array_equal(new_v[i], np.broadcast_to(b_v, (L, cfg.n_kv_heads, hd)))
+        # position 0 is not rotated: the first new key of a fresh prompt is the key bias
+        assert np.allclose(new_k[i][0], w["b_qkv"][q_dim:q_dim + kv_dim].reshape(cfg.n_kv_heads, hd), atol=1e-14)
