@@ -69,7 +69,7 @@ def build_model(cfg, seed, n_layers=None):
 
 
 # ------------------------------------------------------------------------------------- short buckets
-def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, tag, config=2):
+def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, tag, config=2, two_streams=False):
     import numpy as np
     import torch
     from paper_2601_11589_amd import api, inputs, runner
@@ -128,6 +128,35 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
            "plan_us": float(np.median(plan_us)), "graph_shapes": [list(k) for k in shapes],
            "graph_capture_s": {f"{k[0]}x{k[1]}": round(sr.capture_s[k], 4) for k in shapes},
            "graph_device_MB": {f"{k[0]}x{k[1]}": round(sr.graphs[k].laps_graph_device_bytes() / 1e6, 2) for k in shapes}}
+    if two_streams:
+        # throughput variant: batches alternate between two streams, each with its own graph instances, so that the
+        # latency-bound kernels of one replay overlap the weight streaming of the other (per-batch latency rises)
+        stream_b = torch.cuda.Stream()
+        sr_b = runner.ShortRunner(ctx, layers, k_pools, v_pools, b.page_table.shape[1], stream_b)
+        for s in staged:
+            sr_b.graph_for(s.len_bucket, s.depth)
+        pair = [(sr, stream), (sr_b, stream_b)]
+        for j, s in enumerate(staged):
+            pair[j % 2][0].run(s)
+        torch.cuda.synchronize()
+        ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in staged]
+        t0 = time.perf_counter()
+        for k in range(steps):
+            for j, s in enumerate(staged):
+                r, st = pair[j % 2]
+                if k == steps - 1:
+                    ev2[j][0].record(st)
+                r.run(s)
+                if k == steps - 1:
+                    ev2[j][1].record(st)
+        torch.cuda.synchronize()
+        wall2 = time.perf_counter() - t0
+        lat2 = []
+        for j, s in enumerate(staged):
+            lat2 += [ev2[j][0].elapsed_time(ev2[j][1])] * s.n_real
+        res["two_streams"] = {"tokens_per_s": T * steps / wall2, "ms_per_step": wall2 / steps * 1e3,
+                              "latency_ms_p50": pct(lat2, 50), "latency_ms_p90": pct(lat2, 90)}
+        sr_b.close()
     if profile_kernels:
         # same kernels, same shapes, un-captured, every launch bracketed by HIP events on its stream
         ctx.laps_prof_enable(True)
@@ -478,6 +507,8 @@ def main():
     ap.add_argument("--no-reprefill", action="store_true", help="skip the multi-turn re-prefill workload (configs[2])")
     ap.add_argument("--no-graph-cost", action="store_true", help="skip the graph capture cost table (7B/14B/32B shapes)")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="short buckets: skip the variant that alternates the replays between two streams")
     ap.add_argument("--loads", type=str, default="0.7",
                     help="dual queue: Poisson arrival rates as fractions of the unified back-to-back service rate")
     ap.add_argument("--long-steps", type=int, default=2)
@@ -513,7 +544,8 @@ def main():
     layers = layers_all[:4]
 
     log("[bench] leg: short buckets (configs[1])")
-    short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short")
+    short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short",
+                      two_streams=not args.no_two_streams)
     g = short.pop("gemm")
     # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
     # plain copy of known size (profiles/short_bucket_gemm_hbm_traffic.md); valid for the default token budget
