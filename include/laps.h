@@ -235,7 +235,8 @@ int laps_prof_read(laps_ctx* ctx, double* ms_out /*[LAPS_K_COUNT]*/, int64_t* co
 double laps_lm_boundary_prefill(double alpha, double beta, double gamma_w);
 double laps_lm_boundary_reprefill(double alpha, double beta, double gamma_w, double gamma_r, double hist_len);
 /* Least-squares fit of (alpha, beta) to t_comp and (gamma_w, gamma_r) to t_mem from n samples (host arrays
- * [n]; any consistent time unit).  coef_out[4] = {alpha, beta, gamma_w, gamma_r}.  EINVAL if n < 2 or the
+ * [n]; any consistent time unit).  coef_out[4] = {alpha, beta, gamma_w, gamma_r}.  Either time array may be NULL:
+ * that half is not fitted and its two outputs are left untouched.  EINVAL if n < 2, both are NULL, or the
  * samples do not vary L and H independently. */
 int laps_lm_fit(int32_t n, const double* new_len, const double* hist_len, const double* t_comp, const double* t_mem,
                 double* coef_out);

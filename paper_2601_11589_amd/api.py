@@ -149,13 +149,13 @@ def laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len) -> float
     return float(lib().laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len))
 
 
-def laps_lm_fit(new_len, hist_len, t_comp, t_mem):
-    """Returns (alpha, beta, gamma_w, gamma_r)."""
-    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (new_len, hist_len, t_comp, t_mem)]
+def laps_lm_fit(new_len, hist_len, t_comp=None, t_mem=None):
+    """Returns (alpha, beta, gamma_w, gamma_r); the pair whose time array is None comes back as NaN."""
+    arrs = [None if a is None else np.ascontiguousarray(a, dtype=np.float64) for a in (new_len, hist_len, t_comp, t_mem)]
     n = len(arrs[0])
-    assert all(len(a) == n for a in arrs)
-    out = (C.c_double * 4)()
-    ptrs = [a.ctypes.data_as(C.POINTER(C.c_double)) for a in arrs]
+    assert all(a is None or len(a) == n for a in arrs)
+    out = (C.c_double * 4)(*([float("nan")] * 4))
+    ptrs = [None if a is None else a.ctypes.data_as(C.POINTER(C.c_double)) for a in arrs]
     _check(lib().laps_lm_fit(C.c_int32(n), *ptrs, out))
     return tuple(float(v) for v in out)
 

@@ -5,6 +5,7 @@
 // and H > 0); the four coefficients are fitted at run time from samples (T_comp, T_mem, L, H).
 #include <cmath>
 #include <cstdint>
+#include <new>
 
 #include "../../include/laps.h"
 
@@ -46,15 +47,22 @@ static int fit2(int n, const double* x1, const double* x2, const double* y, doub
 
 extern "C" int laps_lm_fit(int32_t n, const double* new_len, const double* hist_len, const double* t_comp,
                            const double* t_mem, double* coef_out) {
-    if (n < 2 || !new_len || !hist_len || !t_comp || !t_mem || !coef_out) {
-        laps_set_error("lm_fit: need at least 2 samples and non-NULL arrays");
+    if (n < 2 || !new_len || !hist_len || (!t_comp && !t_mem) || !coef_out) {
+        laps_set_error("lm_fit: need at least 2 samples, L, H, one of the two time arrays and an output");
         return LAPS_EINVAL;
     }
-    double* q = new double[(size_t)n];
-    for (int i = 0; i < n; ++i) q[i] = new_len[i] * (new_len[i] + 2.0 * hist_len[i]);
-    const int ok1 = fit2(n, q, new_len, t_comp, &coef_out[0], &coef_out[1]);
-    const int ok2 = fit2(n, new_len, hist_len, t_mem, &coef_out[2], &coef_out[3]);
-    delete[] q;
+    int ok1 = 1, ok2 = 1;
+    if (t_comp) {
+        double* q = new (std::nothrow) double[(size_t)n];
+        if (!q) {
+            laps_set_error("lm_fit: out of host memory");
+            return LAPS_ENOMEM;
+        }
+        for (int i = 0; i < n; ++i) q[i] = new_len[i] * (new_len[i] + 2.0 * hist_len[i]);
+        ok1 = fit2(n, q, new_len, t_comp, &coef_out[0], &coef_out[1]);
+        delete[] q;
+    }
+    if (t_mem) ok2 = fit2(n, new_len, hist_len, t_mem, &coef_out[2], &coef_out[3]);
     if (!ok1 || !ok2) {
         laps_set_error("lm_fit: samples do not determine the coefficients (vary L and H independently)");
         return LAPS_EINVAL;

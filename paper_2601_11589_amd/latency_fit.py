@@ -96,11 +96,11 @@ def fit_and_boundaries(samples, cfg, n_layers: int, comp_min_len: int = 256, rep
     L = np.array([s["L"] for s in comp], np.float64)
     H = np.array([s["H"] for s in comp], np.float64)
     tc = np.array([s["t_comp_us"] for s in comp])
-    alpha, beta, _, _ = api.laps_lm_fit(L, H, tc, np.ones_like(tc) * L + H)       # memory columns unused here
+    alpha, beta, _, _ = api.laps_lm_fit(L, H, t_comp=tc)
     La = np.array([s["L"] for s in samples], np.float64)
     Ha = np.array([s["H"] for s in samples], np.float64)
     tm = np.array([s["t_mem_us"] for s in samples])
-    _, _, gamma_w, gamma_r = api.laps_lm_fit(La, Ha, La * (La + 2 * Ha) + La, tm)   # compute columns unused here
+    _, _, gamma_w, gamma_r = api.laps_lm_fit(La, Ha, t_mem=tm)
     pred = alpha * L * (L + 2 * H) + beta * L
     r2_c = 1.0 - float(np.sum((tc - pred) ** 2) / np.sum((tc - tc.mean()) ** 2))
     predm = gamma_w * La + gamma_r * Ha

@@ -56,6 +56,10 @@ def test_library_fit_matches_lstsq_and_recovers_planted_coefficients():
         api.laps_lm_fit(L, 2 * L, tc, tm)            # H proportional to L: gamma_w and gamma_r not separable
     with pytest.raises(api.LapsError):
         api.laps_lm_fit(L[:1], H[:1], tc[:1], tm[:1])
+    half = api.laps_lm_fit(L, H, t_mem=tm)                 # one half only: the other pair is not touched
+    assert math.isnan(half[0]) and math.isnan(half[1]) and half[2:] == pytest.approx((gw, gr), rel=1e-8)
+    with pytest.raises(api.LapsError):
+        api.laps_lm_fit(L, H)
 
 
 def test_fit_and_boundaries_on_planted_samples():
