@@ -124,3 +124,27 @@ def test_host_objects_under_address_and_ub_sanitizers(repo_root, tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
     run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=180)
     assert run.returncode == 0 and run.stdout.strip().endswith("OK"), (run.stdout[-500:], run.stderr[-2000:])
+
+
+def test_public_header_is_plain_c99(repo_root, tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with no C++ or torch types in it, and a C program
+    linked against the library must be able to call a host entry point."""
+    src = tmp_path / "hdr.c"
+    src.write_text(f'#include "{os.path.join(repo_root, "include", "laps.h")}"\n'
+                   "#include <stdio.h>\n"
+                   "int main(void) {\n"
+                   "    int32_t lb[2] = {16, 32}, dp[3] = {1, 2, 4}, nl[3] = {5, 20, 100}, pl[3] = {0, 7, 0};\n"
+                   "    laps_plan_params p = {32, 2, lb, 3, dp, 64, 64};\n"
+                   "    laps_plan* plan = 0;\n"
+                   "    if (laps_plan_buckets(&p, 3, nl, pl, &plan) != LAPS_OK) return 1;\n"
+                   "    printf(\"%d %d %f\\n\", laps_plan_n_batches(plan), laps_plan_n_long(plan), laps_lm_boundary_prefill(1.0, 2.0, 10.0));\n"
+                   "    laps_plan_free(plan);\n"
+                   "    return 0;\n"
+                   "}\n")
+    exe = str(tmp_path / "hdr")
+    libdir = os.path.join(repo_root, "paper_2601_11589_amd")
+    build = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", str(src), "-o", exe,
+                            f"-L{libdir}", "-llaps", f"-Wl,-rpath,{libdir}"], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and run.stdout.split() == ["2", "1", "8.000000"], (run.stdout, run.stderr)
