@@ -201,6 +201,30 @@ def test_tiny_stack_with_qkv_bias():
         ctx0.close()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_ragged_batches_match_oracle(seed):
+    """Seeded random batches at the tiny shape: 1-40 sequences, new lengths 1-150 (a few up to 600), prefixes 0-2500
+    with page-boundary cases, so that skinny and wide GEMM tiles, 128- and 256-row attention blocks and the
+    key-split path all occur; stack output and appended KV against the oracle."""
+    rng = np.random.default_rng(8800 + seed)
+    cfg = inputs.tiny_cfg(2)
+    ctx = api.LapsCtx(cfg, max_positions=4096)
+    for rep in range(4):
+        n = int(rng.integers(1, 41)) if rep else 1
+        new_len = rng.integers(1, 151, n)
+        if rng.random() < 0.5:
+            new_len[rng.integers(n)] = int(rng.integers(150, 601))
+        prefix = np.where(rng.random(n) < 0.4, 0, rng.choice([1, 15, 16, 17, 63, 64, 65, 255, 256, 1000, 2500], n))
+        if n <= 3:
+            prefix[0] = int(rng.choice([0, 2047, 2500]))      # few rows over a long prefix: key-split attention
+        case = Case(cfg, new_len, prefix, 5000 + 10 * seed + rep).to_device(ctx)
+        y_gpu = case.run_stack()
+        _, ks, vs = check_stack(case, y_gpu, f"random batch seed {seed} rep {rep}: lens {list(new_len)} prefixes {list(prefix)}")
+        k_gpu, v_gpu = case.gathered_new_kv(1)
+        assert errors(k_gpu, np.concatenate(ks[1]))[0] < 6e-3 and errors(v_gpu, np.concatenate(vs[1]))[0] < 6e-3
+    ctx.close()
+
+
 def test_cached_prefix_equals_full_prefill_on_device():
     """prefill(prefix || new) == prefill(prefix) followed by re-prefill(new) over the cache written by the first."""
     cfg = inputs.tiny_cfg(2)
