@@ -292,11 +292,16 @@ def test_batch_order_and_padding_do_not_change_rows():
     ctx.close()
 
 
-def test_graph_replays_match_uncaptured_path():
+@pytest.mark.parametrize("prefixes", [[0, 33, 100, 7, 16, 250, 0], [0, 2033, 100, 700, 16, 2500, 0]],
+                         ids=["short_prefixes", "long_prefixes_key_split"])
+def test_graph_replays_match_uncaptured_path(prefixes):
+    """Replays of one captured (16, 4) graph with different slot fillings are bit-equal to the un-captured path on the
+    same padded layout.  With the long prefixes the page table is wide enough for the key-split attention: its
+    grid is fixed at capture, how many splits a slot uses changes from replay to replay."""
     cfg = inputs.tiny_cfg(2)
-    ctx = api.LapsCtx(cfg, max_positions=512)
+    ctx = api.LapsCtx(cfg, max_positions=4096)
     Lb, depth = 16, 4
-    case = Case(cfg, [16, 3, 9, 12, 1, 16, 5], [0, 33, 100, 7, 16, 250, 0], 1234).to_device(ctx)
+    case = Case(cfg, [16, 3, 9, 12, 1, 16, 5], prefixes, 1234).to_device(ctx)
     max_pages = case.page_table.shape[1]
     stream = torch.cuda.Stream()
     graph = ctx.laps_graph_capture(case.dev_layers, Lb, depth, max_pages, case.k_pools, case.v_pools, stream)
