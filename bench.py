@@ -158,21 +158,21 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
                               "latency_ms_p50": pct(lat2, 50), "latency_ms_p90": pct(lat2, 90)}
         sr_b.close()
     if profile_kernels:
-        # same kernels, same shapes, un-captured, every launch bracketed by HIP events on its stream
+        # same kernels, same launch shapes as the graph (its depth slots and depth * len_bucket rows, the requests
+        # packed at the front), un-captured, every launch bracketed by HIP events on its stream
         ctx.laps_prof_enable(True)
         padded = []
         for s in staged:
             M = s.depth * s.len_bucket
             x = torch.zeros((M, cfg.hidden), dtype=torch.float32, device="cuda")
-            x[: s.x_rows.shape[0]] = s.x_rows
-            sl = torch.zeros(s.depth, dtype=torch.int32, device="cuda")
-            sl[: s.n_real] = s.seq_len
+            x[: s.real_tokens] = s.x_rows
             pl = torch.zeros(s.depth, dtype=torch.int32, device="cuda")
             pl[: s.n_real] = s.prefix_len
             pt = torch.zeros((s.depth, s.page_table.shape[1]), dtype=torch.int32, device="cuda")
             pt[: s.n_real] = s.page_table
-            cu = torch.arange(0, (s.depth + 1) * s.len_bucket, s.len_bucket, dtype=torch.int32, device="cuda")
-            padded.append((cu, sl, pl, pt, x, M))
+            cu = torch.full((s.depth + 1,), s.real_tokens, dtype=torch.int32, device="cuda")
+            cu[: s.n_real + 1] = s.cu
+            padded.append((cu, None, pl, pt, x, M))
         torch.cuda.synchronize()
         gbytes = 0.0
         gflops = 0.0
@@ -189,9 +189,10 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
                     acc[0] += v[0]
                     acc[1] += v[1]
                 by, fl = 0.0, 0.0
+                R = sb.real_tokens                     # rows past the packed requests are neither loaded nor stored
                 for (n, kk) in gemm_shapes(cfg).values():
-                    by += cfg.n_layers * (n * kk * 2 + M * kk * 2 + M * n * 4)
-                    fl += cfg.n_layers * 2.0 * M * n * kk
+                    by += cfg.n_layers * (n * kk * 2 + R * kk * 2 + R * n * 4)
+                    fl += cfg.n_layers * 2.0 * R * n * kk
                 gbytes += by
                 gflops += fl
                 ps = per_shape.setdefault(f"{sb.len_bucket}x{sb.depth}", [0.0, 0.0, 0.0, 0])
@@ -202,7 +203,7 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
         ctx.laps_prof_enable(False)
         prof = {k: (v[0], v[1]) for k, v in prof.items()}
         # both roofline fractions of the four projections for every captured shape
-        res["gemm_per_shape"] = {k: {"batches": v[3], "rows": int(k.split("x")[0]) * int(k.split("x")[1]),
+        res["gemm_per_shape"] = {k: {"batches": v[3], "graph_rows": int(k.split("x")[0]) * int(k.split("x")[1]),
                                      "hbm_frac": v[1] / (v[0] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                      "mfma_frac": v[2] / (v[0] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFS}
                                  for k, v in per_shape.items()}

@@ -178,22 +178,29 @@ int laps_prefill_stack(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq
 
 /* ------------------------------------------------------------------ captured short buckets
  * Section 3.1: one graph per (length bucket L_b, depth B_d) with fixed operator topology and
- * variable memory contents.  The graph runs the whole stack on a padded [depth*len_bucket, hidden]
- * batch whose lengths, prefix lengths and page table live in staging buffers the graph owns, so a
- * replay needs no node updates.  Slot b owns rows b*len_bucket .. (b+1)*len_bucket-1.
+ * variable memory contents.  The graph runs the whole stack on up to depth sequences of up to
+ * len_bucket tokens each, held packed (sequence after sequence, no padding between them) in a
+ * [depth*len_bucket, hidden] buffer; lengths, row offsets, prefix lengths and page table live in
+ * staging buffers the graph owns and every kernel reads them from there, so a replay needs no node
+ * updates.  Rows past the staged total are padding: their contents are never used and their output
+ * rows are unspecified (kernels skip them wherever a whole row or row tile is padding).
  * laps_graph_capture allocates the staging buffers and workspace, runs one warm-up pass on the
  * stream with all slots empty, captures and instantiates.  It synchronises the stream. */
 int laps_graph_capture(laps_ctx* ctx, const laps_layer_weights* w, int32_t len_bucket, int32_t depth,
                        int32_t max_pages, void* const* k_pools, void* const* v_pools, void* stream,
                        laps_graph** out);
 /* Fills slots 0..n_real-1 (n_real <= depth; remaining slots become empty).  All pointers are
- * device pointers: seq_len_dev, prefix_len_dev [n_real]; page_table_dev [n_real, max_pages] with
- * row stride max_pages; x_rows_dev fp32 [n_real*len_bucket, hidden] already laid out slot by slot
- * (rows beyond a slot's seq_len may hold anything finite).  Enqueues device-to-device copies. */
+ * device pointers: seq_len_dev, prefix_len_dev [n_real] (a length is clamped to [0, len_bucket] on
+ * the device); page_table_dev [n_real, max_pages] with row stride max_pages; x_rows_dev fp32
+ * [n_rows, hidden], the sequences' rows packed in slot order, n_rows = the sum of the lengths
+ * (0 <= n_rows <= depth*len_bucket, else LAPS_EINVAL; x_rows_dev may be NULL when n_rows is 0, e.g.
+ * when the caller wrote laps_graph_input() in place).  Enqueues one metadata kernel and
+ * device-to-device copies. */
 int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
-                     const int32_t* page_table_dev, const float* x_rows_dev, void* stream);
+                     const int32_t* page_table_dev, const float* x_rows_dev, int32_t n_rows, void* stream);
 int laps_graph_replay(laps_graph* g, void* stream);
-/* Device pointer to the graph's output rows, fp32 [depth*len_bucket, hidden], valid until destroy. */
+/* Device pointer to the graph's output rows, fp32 [depth*len_bucket, hidden], packed like the input; rows
+ * past the staged total hold unspecified values.  Valid until destroy. */
 const float* laps_graph_output(const laps_graph* g);
 /* Device pointer to the graph's input rows (same shape) for callers that write inputs in place. */
 float* laps_graph_input(laps_graph* g);

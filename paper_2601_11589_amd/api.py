@@ -444,9 +444,11 @@ class LapsGraph:
                                         C.c_void_p(stream.cuda_stream), C.byref(self._h)))
 
     def laps_graph_stage(self, n_real, seq_len, prefix_len, page_table, x_rows, stream=None):
+        """x_rows: fp32 [sum of the lengths, hidden] on the device, the sequences packed in slot order (or None)."""
         assert page_table is None or page_table.shape[1] == self.max_pages
+        n_rows = 0 if x_rows is None else int(x_rows.shape[0])
         _check(lib().laps_graph_stage(self._h, C.c_int32(n_real), _p(seq_len), _p(prefix_len), _p(page_table), _p(x_rows),
-                                      _stream(stream)))
+                                      C.c_int32(n_rows), _stream(stream)))
 
     def laps_graph_replay(self, stream=None):
         _check(lib().laps_graph_replay(self._h, _stream(stream)))

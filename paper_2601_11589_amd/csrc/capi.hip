@@ -217,13 +217,13 @@ struct BatchDesc {
 // One projection.  `want` is the epilogue the caller would like fused; the plan falls back to raw
 // K-slice partial sums when it splits K.  Returns the plan so the caller knows which case ran.
 static int run_gemm(laps_ctx* c, int cls, bool capturing, const bf16_t* a, const bf16_t* w, int m, int n, int k,
-                    int want, float* partial, float* out_f32, const float* resid, bf16_t* out_bf16, GemmPlan* plan,
-                    hipStream_t s) {
+                    int want, float* partial, float* out_f32, const float* resid, bf16_t* out_bf16, const int* row_live,
+                    GemmPlan* plan, hipStream_t s) {
     const GemmPlan p = laps_gemm_plan(m, n, k, 0, want);
     *plan = p;
     ProfScope ps(c, s, cls, capturing);
-    if (p.epi == EPI_PARTIAL) return laps_gemm_launch(p, a, w, m, n, k, partial, nullptr, nullptr, s);
-    return laps_gemm_launch(p, a, w, m, n, k, out_f32, resid, out_bf16, s);
+    if (p.epi == EPI_PARTIAL) return laps_gemm_launch(p, a, w, m, n, k, partial, nullptr, nullptr, row_live, s);
+    return laps_gemm_launch(p, a, w, m, n, k, out_f32, resid, out_bf16, row_live, s);
 }
 
 // Runs layers [0, n_layers) of `w`.  Token metadata (prep) is computed once.
@@ -257,7 +257,7 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
     }
     {
         ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
-        LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, s));
+        LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, tok_pos, s));
     }
     for (int l = 0; l < n_layers; ++l) {
         const laps_layer_weights& lw = w[l];
@@ -267,7 +267,7 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         GemmPlan gp;
         // q, k, v: GEMM -> K-slice sums -> bias + RoPE + KV append
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r, static_cast<const bf16_t*>(lw.w_qkv), M, qkv, d, EPI_PARTIAL,
-                          partial, nullptr, nullptr, nullptr, &gp, s));
+                          partial, nullptr, nullptr, nullptr, tok_pos, &gp, s));
         {
             ProfScope ps(c, s, LAPS_K_EPI_QKV, capturing);
             LAPS_TRY(laps_launch_epi_qkv(partial, gp.split, cf.has_qkv_bias ? static_cast<const bf16_t*>(lw.b_qkv) : nullptr,
@@ -281,34 +281,34 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         }
         // x_mid = resid + attn W_o^T ; r = rmsnorm(x_mid; ln2)
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), M, d, qd, EPI_RESID,
-                          partial, x_mid, resid, nullptr, &gp, s));
+                          partial, x_mid, resid, nullptr, tok_pos, &gp, s));
         if (gp.epi == EPI_RESID) {
             ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
-            LAPS_TRY(laps_launch_rmsnorm(x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d, cf.rms_eps, s));
+            LAPS_TRY(laps_launch_rmsnorm(x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d, cf.rms_eps, tok_pos, s));
         } else {
             ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
             LAPS_TRY(laps_launch_epi_resid(partial, gp.split, resid, x_mid, static_cast<const bf16_t*>(lw.ln2_w), r, M, d,
-                                           cf.rms_eps, s));
+                                           cf.rms_eps, tok_pos, s));
         }
         // act = silu(r W_g^T) * (r W_u^T)
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_GATEUP, capturing, r, static_cast<const bf16_t*>(lw.w_gate_up), M, 2 * I, d,
-                          EPI_SWIGLU, partial, nullptr, nullptr, act, &gp, s));
+                          EPI_SWIGLU, partial, nullptr, nullptr, act, tok_pos, &gp, s));
         if (gp.epi != EPI_SWIGLU) {
             ProfScope ps(c, s, LAPS_K_EPI_SWIGLU, capturing);
-            LAPS_TRY(laps_launch_epi_swiglu(partial, gp.split, act, M, I, s));
+            LAPS_TRY(laps_launch_epi_swiglu(partial, gp.split, act, M, I, tok_pos, s));
         }
         // x_out = x_mid + act W_d^T ; r = rmsnorm(x_out; next layer's ln1)
         const bf16_t* next_ln = (l + 1 < n_layers) ? static_cast<const bf16_t*>(w[l + 1].ln1_w) : nullptr;
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_DOWN, capturing, act, static_cast<const bf16_t*>(lw.w_down), M, d, I, EPI_RESID,
-                          partial, x_out, x_mid, nullptr, &gp, s));
+                          partial, x_out, x_mid, nullptr, tok_pos, &gp, s));
         if (gp.epi == EPI_RESID) {
             if (next_ln) {
                 ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
-                LAPS_TRY(laps_launch_rmsnorm(x_out, next_ln, r, M, d, cf.rms_eps, s));
+                LAPS_TRY(laps_launch_rmsnorm(x_out, next_ln, r, M, d, cf.rms_eps, tok_pos, s));
             }
         } else {
             ProfScope ps(c, s, LAPS_K_EPI_RESID, capturing);
-            LAPS_TRY(laps_launch_epi_resid(partial, gp.split, x_mid, x_out, next_ln, r, M, d, cf.rms_eps, s));
+            LAPS_TRY(laps_launch_epi_resid(partial, gp.split, x_mid, x_out, next_ln, r, M, d, cf.rms_eps, tok_pos, s));
         }
     }
     return LAPS_OK;
@@ -440,14 +440,14 @@ extern "C" int laps_gemm_bf16(laps_ctx* c, const void* a, const void* w, float* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const GemmPlan p = laps_gemm_plan(m, n, k, split_k, EPI_PARTIAL);
     if (p.split == 1)
-        return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, out, nullptr, nullptr, s);
+        return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, out, nullptr, nullptr, nullptr, s);
     const size_t need = (size_t)p.split * m * n * sizeof(float);
     if (!ws || ws_bytes < need || ((uintptr_t)ws & 255)) {
         laps_set_error("gemm: split-K needs %zu bytes of 256-byte aligned workspace", need);
         return LAPS_ENOMEM;
     }
     LAPS_TRY(laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, static_cast<float*>(ws),
-                              nullptr, nullptr, s));
+                              nullptr, nullptr, nullptr, s));
     // sum the slices: view [m, n] as rows of `cols` columns, cols | n and cols <= 8192
     int cols = n;
     while (cols > 8192) {
@@ -458,7 +458,7 @@ extern "C" int laps_gemm_bf16(laps_ctx* c, const void* a, const void* w, float* 
         cols /= 2;
     }
     const int rows = (int)(((size_t)m * n) / cols);
-    return laps_launch_epi_resid(static_cast<const float*>(ws), p.split, nullptr, out, nullptr, nullptr, rows, cols, 1.f, s);
+    return laps_launch_epi_resid(static_cast<const float*>(ws), p.split, nullptr, out, nullptr, nullptr, rows, cols, 1.f, nullptr, s);
 }
 
 extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* seq_len,
@@ -562,12 +562,9 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
     g->prefix_len = reinterpret_cast<int*>(g->block + o_pl);
     g->page_table = reinterpret_cast<int*>(g->block + o_pt);
     g->ws = g->block + o_ws;
-    // all slots empty, inputs zero; done before capture, so plain memset / memcpy are fine here
-    std::vector<int> rs(depth + 1);
-    for (int b = 0; b <= depth; ++b) rs[b] = b * len_bucket;
-    if ((e = hipMemsetAsync(g->block, 0, o_ws, s)) != hipSuccess ||
-        (e = hipMemcpyAsync(g->row_start, rs.data(), rs.size() * 4, hipMemcpyHostToDevice, s)) != hipSuccess ||
-        (e = hipStreamSynchronize(s)) != hipSuccess) {
+    // all slots empty (every row offset 0, every length 0), inputs zero; done before capture, so a plain
+    // memset is fine here
+    if ((e = hipMemsetAsync(g->block, 0, o_ws, s)) != hipSuccess || (e = hipStreamSynchronize(s)) != hipSuccess) {
         laps_set_error("graph_capture: staging init failed: %s", hipGetErrorString(e));
         return fail(LAPS_EHIP);
     }
@@ -600,18 +597,21 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
 }
 
 extern "C" int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* seq_len, const int32_t* prefix_len,
-                                const int32_t* page_table, const float* x_rows, void* stream) {
+                                const int32_t* page_table, const float* x_rows, int32_t n_rows, void* stream) {
     if (!g || n_real < 0 || n_real > g->depth || (n_real > 0 && (!seq_len || !prefix_len || !page_table))) {
         laps_set_error("graph_stage: bad slot count or NULL pointer");
         return LAPS_EINVAL;
     }
+    if (n_rows < 0 || n_rows > g->depth * g->len_bucket || (n_rows > 0 && !x_rows)) {
+        laps_set_error("graph_stage: %d input rows do not fit the graph's %d rows", n_rows, g->depth * g->len_bucket);
+        return LAPS_EINVAL;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    LAPS_TRY(laps_launch_copy_i32(g->seq_len, seq_len, n_real, n_real, 0, g->depth, s));
-    LAPS_TRY(laps_launch_copy_i32(g->prefix_len, prefix_len, n_real, n_real, 0, g->depth, s));
+    LAPS_TRY(laps_launch_stage_meta(seq_len, prefix_len, n_real, g->depth, g->len_bucket, g->seq_len, g->prefix_len,
+                                    g->row_start, s));
     LAPS_TRY(laps_launch_copy_i32(g->page_table, page_table, n_real * g->max_pages, 0, 0, g->depth * g->max_pages, s));
-    if (x_rows && n_real > 0)
-        LAPS_HIP(hipMemcpyAsync(g->x_in, x_rows, (size_t)n_real * g->len_bucket * g->ctx->cfg.hidden * 4,
-                                hipMemcpyDeviceToDevice, s));
+    if (n_rows > 0)
+        LAPS_HIP(hipMemcpyAsync(g->x_in, x_rows, (size_t)n_rows * g->ctx->cfg.hidden * 4, hipMemcpyDeviceToDevice, s));
     return LAPS_OK;
 }
 

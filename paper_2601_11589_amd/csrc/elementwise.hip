@@ -41,8 +41,8 @@ __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_s
     if (row < n_seq) {
         const int cap = row_start[row + 1] - row_start[row];
         int l = seq_len ? seq_len[row] : cap;
-        l = l < 0 ? 0 : (l > cap ? cap : l);
-        new_len_out[row] = l;
+        l = l > cap ? cap : l;
+        new_len_out[row] = l < 0 ? 0 : l;
     }
     if (row >= n_rows) return;
     int lo = 0, hi = n_seq;  // find s with row_start[s] <= row < row_start[s+1]
@@ -68,9 +68,10 @@ __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_s
 // ------------------------------------------------------------------ RMSNorm: fp32 row -> bf16 row
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x,
                                                                const bf16_t* __restrict__ w, bf16_t* __restrict__ out,
-                                                               int d, float eps) {
+                                                               int d, float eps, const int* __restrict__ row_live) {
     __shared__ float red[ROW_THREADS / 64];
     const size_t row = blockIdx.x;
+    if (row_live && row_live[row] < 0) return;  // padding row: nothing reads its output
     const f32x4* xr = reinterpret_cast<const f32x4*>(x + row * d);
     float ss = 0.f;
     for (int i = threadIdx.x; i < d / 4; i += ROW_THREADS) {
@@ -113,9 +114,11 @@ __global__ __launch_bounds__(RESID_THREADS) void epi_resid_kernel(const float* _
                                                                    size_t slice_stride, const float* __restrict__ resid,
                                                                    float* __restrict__ x_out,
                                                                    const bf16_t* __restrict__ ln_w,
-                                                                   bf16_t* __restrict__ r_out, int d, float eps) {
+                                                                   bf16_t* __restrict__ r_out, int d, float eps,
+                                                                   const int* __restrict__ row_live) {
     __shared__ float red[RESID_THREADS / 64];
     const size_t row = blockIdx.x;
+    if (row_live && row_live[row] < 0) return;  // padding row
     const int nv = d / 4;
     f32x4 v[MAXV];
     float ss = 0.f;
@@ -179,6 +182,14 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __res
     const int width = (n_q + 2 * n_kv) * hd;
     const int head = it / per_head, j = (it % per_head) * 4;
     const int c0 = head * hd + j, c1 = c0 + half;
+    if (pos < 0 || slot < 0) {  // padding row: defined q (zero), no cache write, partial sums not read
+        if (head < n_q) {
+            const u32x2 z = {0u, 0u};
+            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c0) = z;
+            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c1) = z;
+        }
+        return;
+    }
     f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
     const float* p = partial + row * width;
     for (int s = 0; s < split; ++s) {
@@ -191,14 +202,6 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __res
             a[e] += bf16_to_f32(bias[c0 + e]);
             b[e] += bf16_to_f32(bias[c1 + e]);
         }
-    }
-    if (pos < 0 || slot < 0) {  // padding row: defined q (zero), no cache write
-        if (head < n_q) {
-            const u32x2 z = {0u, 0u};
-            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c0) = z;
-            *reinterpret_cast<u32x2*>(q_out + row * (size_t)(n_q * hd) + c1) = z;
-        }
-        return;
     }
     if (head < n_q + n_kv) {
         // positions past the table are the caller's error; clamp so that the read stays in bounds
@@ -241,9 +244,10 @@ __global__ __launch_bounds__(ROW_THREADS) void epi_qkv_kernel(const float* __res
 // Packed gate/up columns: block b of 64 columns = gate cols [32b, 32b+32) then up cols [32b, 32b+32).
 __global__ __launch_bounds__(ROW_THREADS) void epi_swiglu_kernel(const float* __restrict__ partial, int split,
                                                                   size_t slice_stride, bf16_t* __restrict__ act,
-                                                                  int inter) {
+                                                                  int inter, const int* __restrict__ row_live) {
     const size_t row = blockIdx.x;
     const int width = 2 * inter;
+    if (row_live && row_live[row] < 0) return;  // padding row
     {
         const int c4 = blockIdx.y * ROW_THREADS + threadIdx.x;
         if (c4 >= inter / 4) return;
@@ -317,7 +321,56 @@ __global__ void copy_fill_i32_kernel(int* __restrict__ dst, const int* __restric
     dst[i] = (i < n) ? src[i] : fill_value;
 }
 
+// Metadata of one captured bucket, from what the caller staged for its first n_real slots: lengths
+// clamped to [0, len_bucket], prefix lengths to >= 0, the other slots empty, and the sequences packed
+// one after the other (row_start = running sum of the clamped lengths, so the total never exceeds the
+// graph's depth * len_bucket rows whatever the caller's arrays hold).  One workgroup; thread t owns a
+// run of consecutive slots.
+constexpr int META_THREADS = 256;
+__global__ __launch_bounds__(META_THREADS) void stage_meta_kernel(const int* __restrict__ seq_len,
+                                                                  const int* __restrict__ prefix_len, int n_real,
+                                                                  int depth, int len_bucket, int* __restrict__ seq_len_out,
+                                                                  int* __restrict__ prefix_out, int* __restrict__ row_start_out) {
+    __shared__ int sums[META_THREADS];
+    const int t = threadIdx.x;
+    const int per = (depth + META_THREADS - 1) / META_THREADS;
+    const int lo = t * per, hi = (lo + per < depth) ? lo + per : depth;
+    auto len_of = [&](int i) {
+        int l = i < n_real ? seq_len[i] : 0;
+        l = l > len_bucket ? len_bucket : l;
+        return l < 0 ? 0 : l;
+    };
+    int mine = 0;
+    for (int i = lo; i < hi; ++i) mine += len_of(i);
+    sums[t] = mine;
+    __syncthreads();
+    for (int o = 1; o < META_THREADS; o <<= 1) {  // inclusive scan of the per-thread sums
+        const int v = (t >= o) ? sums[t - o] : 0;
+        __syncthreads();
+        sums[t] += v;
+        __syncthreads();
+    }
+    int run = sums[t] - mine;
+    for (int i = lo; i < hi; ++i) {
+        const int l = len_of(i);
+        row_start_out[i] = run;
+        seq_len_out[i] = l;
+        const int pf = i < n_real ? prefix_len[i] : 0;
+        prefix_out[i] = pf < 0 ? 0 : pf;
+        run += l;
+    }
+    if (t == META_THREADS - 1) row_start_out[depth] = sums[t];
+}
+
 }  // namespace
+
+int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
+                           int* seq_len_out, int* prefix_out, int* row_start_out, hipStream_t s) {
+    hipLaunchKernelGGL(stage_meta_kernel, dim3(1), dim3(META_THREADS), 0, s, seq_len, prefix_len, n_real, depth,
+                       len_bucket, seq_len_out, prefix_out, row_start_out);
+    LAPS_LAUNCH_CHECK();
+    return LAPS_OK;
+}
 
 int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s) {
     const int half = head_dim / 2;
@@ -338,21 +391,22 @@ int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq
     return LAPS_OK;
 }
 
-int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, hipStream_t s) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, x, w, out, d, eps);
+int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, const int* row_live,
+                        hipStream_t s) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(ROW_THREADS), 0, s, x, w, out, d, eps, row_live);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
 
 int laps_launch_epi_resid(const float* partial, int split, const float* resid, float* x_out, const bf16_t* ln_w,
-                          bf16_t* r_out, int rows, int d, float eps, hipStream_t s) {
+                          bf16_t* r_out, int rows, int d, float eps, const int* row_live, hipStream_t s) {
     const size_t stride = (size_t)rows * d;
     if (d <= 4 * RESID_THREADS * 1)
         hipLaunchKernelGGL(epi_resid_kernel<1>, dim3(rows), dim3(RESID_THREADS), 0, s, partial, split, stride, resid,
-                           x_out, ln_w, r_out, d, eps);
+                           x_out, ln_w, r_out, d, eps, row_live);
     else if (d <= 4 * RESID_THREADS * 4)
         hipLaunchKernelGGL(epi_resid_kernel<4>, dim3(rows), dim3(RESID_THREADS), 0, s, partial, split, stride, resid,
-                           x_out, ln_w, r_out, d, eps);
+                           x_out, ln_w, r_out, d, eps, row_live);
     else {
         laps_set_error("row width %d too large for the fused residual + norm kernel (max %d)", d, 4 * RESID_THREADS * 4);
         return LAPS_EINVAL;
@@ -373,10 +427,11 @@ int laps_launch_epi_qkv(const float* partial, int split, const bf16_t* bias, con
     return LAPS_OK;
 }
 
-int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, hipStream_t s) {
+int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, const int* row_live,
+                           hipStream_t s) {
     const size_t stride = (size_t)rows * 2 * inter;
     hipLaunchKernelGGL(epi_swiglu_kernel, dim3(rows, (inter / 4 + ROW_THREADS - 1) / ROW_THREADS), dim3(ROW_THREADS), 0,
-                       s, partial, split, stride, act, inter);
+                       s, partial, split, stride, act, inter, row_live);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }

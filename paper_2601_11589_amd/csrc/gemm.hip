@@ -77,6 +77,8 @@ struct GemmArgs {
     float* out_f32;        // EPI_PARTIAL: [split][M][N]; EPI_RESID: [M][N]
     const float* resid;    // EPI_RESID: [M][N] (may alias out_f32)
     bf16_t* out_bf16;      // EPI_SWIGLU: [M][N/2]
+    const int* row_live;   // [M] or NULL: rows with a negative entry are padding - skinny tiles skip their A loads,
+                           // every tile shape skips a row tile that holds nothing else (its output is then not written)
 };
 
 // WS = number of register sets that stage slabs: WS slabs (A and W chunks alike - loads return in
@@ -99,6 +101,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
 
     constexpr bool NT = (BM <= 128);  // skinny tiles only
     const int tid = threadIdx.x;
+    if (g.row_live != nullptr) {  // a row tile made of padding only has nothing to compute (and nothing reads its output)
+        bool any = false;
+        for (int r = tid; r < BM; r += T::NT) any |= (m0 + r < M) && g.row_live[m0 + r] >= 0;
+        if (!__syncthreads_or(any)) return;
+    }
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lk = lane >> 5;
@@ -107,12 +114,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     const u32x4* ag[T::A_LOADS];
     const u32x4* bg[T::B_LOADS];
     int a_dst[T::A_LOADS], b_dst[T::B_LOADS];
+    // Skinny tiles: a CU keeps a bounded number of requests in flight, and the A slab's share of them
+    // (a third with 256 columns) is taken from the weight stream; rows past M and padding rows are
+    // therefore not loaded at all - their staging registers stay zero.
+    bool a_live[T::A_LOADS];
 #pragma unroll
     for (int i = 0; i < T::A_LOADS; ++i) {
         const int c = tid + i * T::NT, row = c / CHUNKS, kc = c % CHUNKS;
         const int gr = (m0 + row < M) ? (m0 + row) : (M - 1);  // clamp: rows past M are never stored
         ag[i] = reinterpret_cast<const u32x4*>(g.A + (size_t)gr * K + kbeg) + kc;
         a_dst[i] = row * CHUNKS + swz(row, kc);
+        a_live[i] = !NT || (m0 + row < M && (g.row_live == nullptr || g.row_live[gr] >= 0));
     }
 #pragma unroll
     for (int i = 0; i < T::B_LOADS; ++i) {
@@ -137,6 +149,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
     u32x4 rra[WS][T::A_LOADS];   // staged A slabs: slab j lives in set j % WS
+    if constexpr (NT) {
+#pragma unroll
+        for (int w = 0; w < WS; ++w)
+#pragma unroll
+            for (int i = 0; i < T::A_LOADS; ++i) rra[w][i] = u32x4{0u, 0u, 0u, 0u};
+    }
     u32x4 rrb[WS][T::B_LOADS];   // staged W slabs, same rule
     bf16x8 fa[2][T::MI], fb[2][T::NI];
     constexpr int NM = T::MI * T::NI;            // MFMAs per k-step
@@ -147,8 +165,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
     auto clampk = [&](int kt) { return kt < KT ? kt : KT - 1; };  // tail: reload a valid slab, never used
     // copy op i of the slab pipeline: i < A_LOADS moves an A chunk, else a W chunk held in set `ws`
     auto gload_one = [&](int i, int kt, int ws) {
-        if (i < T::A_LOADS) rra[ws][i] = ag[i][clampk(kt) * CHUNKS];
-        else {
+        if (i < T::A_LOADS) {
+            if constexpr (NT) {
+                if (a_live[i]) rra[ws][i] = ag[i][clampk(kt) * CHUNKS];
+            } else {
+                rra[ws][i] = ag[i][clampk(kt) * CHUNKS];
+            }
+        } else {
             // weights are read once: streaming (non-temporal) loads keep them from evicting the A slabs,
             // which every workgroup on the CU and on the XCD re-reads, out of L1 / L2
             const u32x4* src = bg[i - T::A_LOADS] + clampk(kt) * CHUNKS;
@@ -412,7 +435,7 @@ size_t laps_gemm_partial_bytes(int m, int n, int k) {
 }
 
 int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
-                     const float* resid, bf16_t* out_bf16, hipStream_t s) {
+                     const float* resid, bf16_t* out_bf16, const int* row_live, hipStream_t s) {
     if (m < 1 || n < 64 || k < BK || k % BK != 0 || p.cfg < 0 || p.cfg >= kNumTiles || n % kTiles[p.cfg].bn != 0) {
         laps_set_error("gemm: unsupported shape m=%d n=%d k=%d for tile %d", m, n, k, p.cfg);
         return LAPS_EINVAL;
@@ -438,6 +461,7 @@ int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m,
     g.out_f32 = out_f32;
     g.resid = resid;
     g.out_bf16 = out_bf16;
+    g.row_live = row_live;
 #define LAPS_TILE_CASE(cfg, BM, BN, WM, WN, EPI, WS) \
     case ((cfg) * 4 + (EPI)) * 8 + (WS): return launch_tile<BM, BN, WM, WN, EPI, WS>(g, s)
     switch ((p.cfg * 4 + p.epi) * 8 + p.ws) {

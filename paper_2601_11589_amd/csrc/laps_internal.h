@@ -56,26 +56,35 @@ struct GemmPlan {
 };
 GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi);
 size_t laps_gemm_partial_bytes(int m, int n, int k);
+// row_live: NULL, or m entries; a negative entry marks a padding row.  Output rows of padding are unspecified:
+// the skinny tiles do not load them (they compute with zeros), and a row tile of padding only is skipped.
 int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
-                     const float* resid, bf16_t* out_bf16, hipStream_t s);
+                     const float* resid, bf16_t* out_bf16, const int* row_live, hipStream_t s);
 
 // ----------------------------------------------------------------------------- element-wise / epilogues
 int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s);
 int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq_len, const int* prefix_len,
                      const int* page_table, int max_pages, int* new_len_out, int* tok_pos, int* tok_slot,
                      hipStream_t s);
-int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, hipStream_t s);
+// row_live (here and below): NULL, or one entry per row; rows with a negative entry are padding and are skipped.
+int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, const int* row_live,
+                        hipStream_t s);
 // x_out = resid + sum_s partial[s]; if ln_w: r_out = rmsnorm(x_out; ln_w) in bf16.
 int laps_launch_epi_resid(const float* partial, int split, const float* resid, float* x_out, const bf16_t* ln_w,
-                          bf16_t* r_out, int rows, int d, float eps, hipStream_t s);
+                          bf16_t* r_out, int rows, int d, float eps, const int* row_live, hipStream_t s);
 int laps_launch_epi_qkv(const float* partial, int split, const bf16_t* bias, const int* tok_pos, const int* tok_slot,
                         const float2* rope, int max_pos, bf16_t* q_out, bf16_t* k_pool, bf16_t* v_pool, int rows,
                         int n_q, int n_kv, int hd, hipStream_t s);
-int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, hipStream_t s);
+int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int rows, int inter, const int* row_live,
+                           hipStream_t s);
 int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, int inter, int d, hipStream_t s);
 int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
                         const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
                         bf16_t* v_pool, int n_kv, int hd, hipStream_t s);
+// Graph staging: clamped lengths / prefixes of `depth` slots (the first n_real from the caller's device arrays, the
+// rest empty) and packed row offsets row_start_out[depth + 1].
+int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
+                           int* seq_len_out, int* prefix_out, int* row_start_out, hipStream_t s);
 int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s);
 
 // ----------------------------------------------------------------------------- attention

@@ -139,13 +139,15 @@ class DualQueue:
         for sb in staged:
             out = None
             if self.out is not None:
-                out = torch.empty((sb.n_real * sb.len_bucket, self.d_x.shape[1]), dtype=torch.float32, device="cuda")
+                out = torch.empty((sb.real_tokens, self.d_x.shape[1]), dtype=torch.float32, device="cuda")
             self.short.graph_for(sb.len_bucket, sb.depth)      # capture (first use) is not part of the step
             us = self._timed(lambda: self.short.run(sb, out))
             if out is not None:
-                for slot, j in enumerate(sb.req_ids):
+                row = 0
+                for j in sb.req_ids:
                     r = ids[j]
-                    self.out[self.cu[r]: self.cu[r + 1]] = out[slot * sb.len_bucket: slot * sb.len_bucket + int(self.new_len[r])]
+                    self.out[self.cu[r]: self.cu[r + 1]] = out[row: row + int(self.new_len[r])]
+                    row += int(self.new_len[r])
                 self.stream.synchronize()
             res.append(([ids[j] for j in sb.req_ids], us))
         return res

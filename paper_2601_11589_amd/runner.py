@@ -16,7 +16,7 @@ from . import api
 
 @dataclass
 class StagedBatch:
-    """Device-resident inputs of one planned short batch, already in the bucket's padded layout."""
+    """Device-resident inputs of one planned short batch: the requests' rows packed one after the other."""
     len_bucket: int
     depth: int
     graph_ok: int
@@ -25,8 +25,8 @@ class StagedBatch:
     seq_len: torch.Tensor      # int32 [n_real]
     prefix_len: torch.Tensor   # int32 [n_real]
     page_table: torch.Tensor   # int32 [n_real, max_pages]
-    x_rows: torch.Tensor       # fp32 [n_real*len_bucket, hidden]  (graph_ok) or packed rows (fallback)
-    cu: torch.Tensor | None    # fallback only: packed cu_seqlens
+    x_rows: torch.Tensor       # fp32 [real_tokens, hidden], packed
+    cu: torch.Tensor           # int32 [n_real + 1] packed cu_seqlens (used by the un-captured path)
     real_tokens: int
 
 
@@ -40,15 +40,9 @@ def stage_short_batches(plan: dict, new_len, prefix_len, page_table, cu, d_x: to
         sl = torch.tensor([int(new_len[i]) for i in ids], dtype=torch.int32, device="cuda")
         pl = torch.tensor([int(prefix_len[i]) for i in ids], dtype=torch.int32, device="cuda")
         pt = torch.from_numpy(np.ascontiguousarray(page_table[ids])).cuda()
-        if b["graph_ok"]:
-            x = torch.zeros((n_real * lb, hidden), dtype=torch.float32, device="cuda")
-            for slot, i in enumerate(ids):
-                x[slot * lb: slot * lb + int(new_len[i])] = d_x[int(cu[i]):int(cu[i + 1])]
-            c = None
-        else:
-            x = torch.cat([d_x[int(cu[i]):int(cu[i + 1])] for i in ids])
-            c = torch.tensor(np.concatenate([[0], np.cumsum([int(new_len[i]) for i in ids])]), dtype=torch.int32,
-                             device="cuda")
+        x = torch.cat([d_x[int(cu[i]):int(cu[i + 1])] for i in ids])
+        c = torch.tensor(np.concatenate([[0], np.cumsum([int(new_len[i]) for i in ids])]), dtype=torch.int32,
+                         device="cuda")
         out.append(StagedBatch(lb, b["depth"], b["graph_ok"], ids, n_real, sl, pl, pt, x, c,
                                int(sum(int(new_len[i]) for i in ids))))
     return out
@@ -80,7 +74,7 @@ class ShortRunner:
             g.laps_graph_stage(sb.n_real, sb.seq_len, sb.prefix_len, sb.page_table, sb.x_rows, self.stream)
             g.laps_graph_replay(self.stream)
             if out is not None:
-                g.laps_graph_read_output(sb.n_real * sb.len_bucket, out, self.stream)
+                g.laps_graph_read_output(sb.real_tokens, out, self.stream)
             return out
         with torch.cuda.stream(self.stream):
             return self.ctx.laps_prefill_stack(self.layers, sb.cu, None, sb.prefix_len, sb.page_table, self.k_pools,

@@ -117,12 +117,14 @@ def run_planned_short(case, cfg, ctx, token_budget, len_buckets=LEN_BUCKETS):
     sr = runner.ShortRunner(ctx, case.dev_layers, case.k_pools, case.v_pools, case.page_table.shape[1], stream)
     ys = {}
     for sb in staged:
-        out = torch.empty((sb.n_real * sb.len_bucket, cfg.hidden), dtype=torch.float32, device="cuda")
+        out = torch.empty((sb.real_tokens, cfg.hidden), dtype=torch.float32, device="cuda")
         sr.run(sb, out)
         stream.synchronize()
         o = out.cpu().numpy()
-        for slot, i in enumerate(sb.req_ids):
-            ys[i] = o[slot * sb.len_bucket: slot * sb.len_bucket + int(case.new_len[i])]
+        row = 0
+        for i in sb.req_ids:
+            ys[i] = o[row: row + int(case.new_len[i])]
+            row += int(case.new_len[i])
     sr.close()
     return ys, plan
 

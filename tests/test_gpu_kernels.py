@@ -295,8 +295,8 @@ def test_batch_order_and_padding_do_not_change_rows():
 @pytest.mark.parametrize("prefixes", [[0, 33, 100, 7, 16, 250, 0], [0, 2033, 100, 700, 16, 2500, 0]],
                          ids=["short_prefixes", "long_prefixes_key_split"])
 def test_graph_replays_match_uncaptured_path(prefixes):
-    """Replays of one captured (16, 4) graph with different slot fillings are bit-equal to the un-captured path on the
-    same padded layout.  With the long prefixes the page table is wide enough for the key-split attention: its
+    """Replays of one captured (16, 4) graph with different slot fillings (rows packed, as the graph holds them) are
+    bit-equal to the un-captured path run on a padded layout of the same 64 rows.  With the long prefixes the page table is wide enough for the key-split attention: its
     grid is fixed at capture, how many splits a slot uses changes from replay to replay."""
     cfg = inputs.tiny_cfg(2)
     ctx = api.LapsCtx(cfg, max_positions=4096)
@@ -323,17 +323,42 @@ def test_graph_replays_match_uncaptured_path(prefixes):
         want = ctx.laps_prefill_stack(case.dev_layers, cu, d_sl, d_pre, d_tab, case.k_pools, case.v_pools, d_x)
         torch.cuda.synchronize()
         with torch.cuda.stream(stream):
+            packed = torch.cat([d_x[slot * Lb: slot * Lb + int(case.new_len[i])] for slot, i in enumerate(ids)])
             graph.laps_graph_stage(n_real, d_sl[:n_real].contiguous(), d_pre[:n_real].contiguous(),
-                                   d_tab[:n_real].contiguous(), d_x[:n_real * Lb].contiguous(), stream)
+                                   d_tab[:n_real].contiguous(), packed, stream)
             graph.laps_graph_replay(stream)
-            got = torch.empty((depth * Lb, cfg.hidden), dtype=torch.float32, device="cuda")
-            graph.laps_graph_read_output(depth * Lb, got, stream)
+            got = torch.empty((packed.shape[0], cfg.hidden), dtype=torch.float32, device="cuda")
+            graph.laps_graph_read_output(packed.shape[0], got, stream)
         stream.synchronize()
+        row = 0
         for slot, i in enumerate(ids):
-            a = got[slot * Lb: slot * Lb + int(case.new_len[i])].cpu().numpy()
-            b = want[slot * Lb: slot * Lb + int(case.new_len[i])].cpu().numpy()
+            n = int(case.new_len[i])
+            a = got[row: row + n].cpu().numpy()
+            b = want[slot * Lb: slot * Lb + n].cpu().numpy()
             assert np.array_equal(a, b), (rep, slot)
+            row += n
     graph.close()
+    ctx.close()
+
+
+def test_graph_stage_clamps_lengths_to_the_bucket():
+    """A staged length above the graph's length bucket is cut to the bucket on the device: rows stay inside the
+    graph's buffers, and the result is that of the cut lengths."""
+    cfg = inputs.tiny_cfg(1)
+    ctx = api.LapsCtx(cfg, max_positions=256)
+    case = Case(cfg, [16, 7], [3, 20], 77).to_device(ctx)
+    want = case.run_stack()
+    stream = torch.cuda.Stream()
+    g = ctx.laps_graph_capture(case.dev_layers, 16, 2, case.page_table.shape[1], case.k_pools, case.v_pools, stream)
+    too_long = torch.tensor([40, 7], dtype=torch.int32, device="cuda")
+    got = torch.empty((23, cfg.hidden), dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(stream):
+        g.laps_graph_stage(2, too_long, case.d_prefix_len, case.d_page_table, case.d_x, stream)
+        g.laps_graph_replay(stream)
+        g.laps_graph_read_output(23, got, stream)
+    stream.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    g.close()
     ctx.close()
 
 
@@ -397,6 +422,8 @@ def test_graph_stage_rejects_too_many_slots_and_empty_replay_is_harmless():
     tab = torch.zeros((3, case.page_table.shape[1]), dtype=torch.int32, device="cuda")
     with pytest.raises(api.LapsError):
         g.laps_graph_stage(3, three, three, tab, None, stream)
+    with pytest.raises(api.LapsError):                          # more input rows than the graph holds
+        g.laps_graph_stage(2, three[:2], three[:2], tab[:2], torch.zeros((33, cfg.hidden), device="cuda"), stream)
     g.laps_graph_stage(0, None, None, None, None, stream)      # all slots empty
     g.laps_graph_replay(stream)
     stream.synchronize()
