@@ -331,6 +331,7 @@ def run_graph_cost(ctx32, layers32):
             seed = inputs.SEED_BASE + 60 + len(name)
             layers = [ctx.upload_layer(inputs.make_layer_weights(cfg, seed, l, threads=min(16, os.cpu_count() or 8)))
                       for l in range(4)]
+        log(f"[bench:graph-cost] {name}-shaped stack")
         max_pages = 16          # a 256-token request fills 16 pages
         k_pools, v_pools = ctx.new_pools(max_pages * 64 + 1, 4, zero=True)
         stream = torch.cuda.Stream()
@@ -347,6 +348,9 @@ def run_graph_cost(ctx32, layers32):
                 sl = torch.full((d,), lb, dtype=torch.int32, device="cuda")
                 pl = torch.zeros(d, dtype=torch.int32, device="cuda")
                 pt = (torch.arange(d * max_pages, dtype=torch.int32, device="cuda") + 1).reshape(d, max_pages).contiguous()
+                # torch filled these on its default stream; `stream` does not wait for that stream by itself, and a
+                # page table read before it is written holds whatever the allocator's block held before
+                torch.cuda.synchronize()
                 g.laps_graph_stage(d, sl, pl, pt, x, stream)
                 g.laps_graph_replay(stream)
                 stream.synchronize()
@@ -419,6 +423,7 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,)):
     dq = dualqueue.DualQueue(ctx8, layers8, b.new_len, b.prefix_len, b.page_table, d_x, k_pools, v_pools,
                              dualqueue.DQParams())
     zeros = np.zeros(b.n)
+    log("[bench:dual-queue] warm-up and back-to-back passes")
     dq.run_disaggregated(zeros, 0.0)          # warm-up: captures every bucket shape the workload needs
     dq.run_unified(zeros)
     u0 = dq.run_unified(zeros)
@@ -550,7 +555,7 @@ def main():
     g = short.pop("gemm")
     # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
     # plain copy of known size (profiles/short_bucket_gemm_hbm_traffic.md); valid for the default token budget
-    traffic = 273.1e6 if args.token_budget == 128 else None
+    traffic = 270.9e6 if args.token_budget == 128 else None
     line = {
         "metric": METRIC, "value": short["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": short["ms_per_step"], "higher_is_better": True, "scaling": "weak",

@@ -24,6 +24,9 @@
  *     stream and never allocate device memory.  The kernels they enqueue read the device arrays
  *     passed in (lengths, page tables, inputs, weights, pools) when they run, not when the call
  *     returns: keep those arrays valid and unchanged until that stream work has completed.
+ *     Arrays written by work on another stream must be complete before the call (event or
+ *     synchronisation on the caller's side): a page table read before it is written makes the
+ *     K/V append write wherever the stale entries point.  Page ids are not range-checked.
  *   - bf16 = upper 16 bits of an IEEE float32, round-to-nearest-even on conversion.
  *   - Layer math (all accumulation fp32): r = rmsnorm(x; ln1); [q,k,v] = r W_qkv^T (+b);
  *     rotate-half RoPE with theta on q,k at absolute position prefix_len+t; causal grouped-
@@ -130,6 +133,12 @@ const int32_t* laps_plan_long_chunk_len(const laps_plan* plan);    /* chunk leng
  * for positions 0..max_positions-1 (device allocation; freed by laps_ctx_destroy). */
 int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions, laps_ctx** out);
 void laps_ctx_destroy(laps_ctx* ctx);
+/* Optional guard for the calls that follow on this context: the K/V pools they are given hold n_pages
+ * pages each.  Page-table entries outside [0, n_pages) are then treated like unset (-1) entries - the
+ * token's K/V is not written and reads fall back to page 0 - instead of addressing memory outside
+ * the pools.  0 switches the check off (the default: the library does not know the pools' size).  A
+ * graph keeps the value that was set when it was captured.  EINVAL on NULL or a negative count. */
+int laps_ctx_set_pool_pages(laps_ctx* ctx, int32_t n_pages);
 /* Bytes of scratch laps_prefill_layer / laps_prefill_stack need for up to max_tokens rows
  * (padded rows count) and max_seqs sequences.  0 on bad arguments. */
 size_t laps_workspace_bytes(const laps_ctx* ctx, int32_t max_tokens, int32_t max_seqs);

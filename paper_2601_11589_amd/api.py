@@ -315,6 +315,11 @@ class LapsCtx:
     def laps_workspace_bytes(self, max_tokens: int, max_seqs: int) -> int:
         return int(lib().laps_workspace_bytes(self._h, C.c_int32(max_tokens), C.c_int32(max_seqs)))
 
+    def _guard_pools(self, pool: torch.Tensor):
+        """Tells the library how many pages the pools of the next call hold, so that a page id outside them (a stale
+        or corrupted table) is ignored instead of addressing memory outside the pools."""
+        _check(lib().laps_ctx_set_pool_pages(self._h, C.c_int32(int(pool.shape[0]))))
+
     def workspace(self, max_tokens: int, max_seqs: int) -> torch.Tensor:
         need = self.laps_workspace_bytes(max_tokens, max_seqs)
         if need == 0:
@@ -357,6 +362,7 @@ class LapsCtx:
 
     def laps_kv_scatter(self, cu, start_pos, page_table, k_src, v_src, k_pool, v_pool, stream=None):
         n_seq, n_tok = cu.numel() - 1, k_src.shape[0]
+        self._guard_pools(k_pool)
         _check(lib().laps_kv_scatter(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(start_pos), _p(page_table),
                                      C.c_int32(page_table.shape[1]), _p(k_src), _p(v_src), _p(k_pool), _p(v_pool),
                                      _stream(stream)))
@@ -366,6 +372,7 @@ class LapsCtx:
         shp = (n_tokens, self.cfg.n_kv_heads, self.cfg.head_dim)
         k = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
         v = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+        self._guard_pools(k_pool)
         _check(lib().laps_kv_gather(self._h, C.c_int32(n_seq), C.c_int32(n_tokens), _p(cu), _p(start_pos), _p(page_table),
                                     C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(k), _p(v), _stream(stream)))
         return k, v
@@ -377,6 +384,7 @@ class LapsCtx:
         x_out = torch.empty_like(x_in) if x_out is None else x_out
         ws = self.workspace(n_tok, n_seq)
         arr = self._weights_array([w])
+        self._guard_pools(k_pool)
         _check(lib().laps_prefill_layer(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                         _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(x_in),
                                         _p(x_out), _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
@@ -390,6 +398,7 @@ class LapsCtx:
         arr = self._weights_array(layers)
         kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
         vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
+        self._guard_pools(k_pools[0])
         _check(lib().laps_prefill_stack(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                         _p(page_table), C.c_int32(page_table.shape[1]), kp, vp, _p(x_in), _p(x_out), _p(ws),
                                         C.c_size_t(ws.numel()), _stream(stream)))
@@ -410,6 +419,7 @@ class LapsCtx:
         n_seq, n_tok = cu.numel() - 1, q.shape[0]
         out = torch.zeros_like(q)
         ws = self.workspace(n_tok, n_seq)
+        self._guard_pools(k_pool)
         _check(lib().laps_attention(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                     _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(q), _p(out),
                                     _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
@@ -440,6 +450,7 @@ class LapsGraph:
         kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
         vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
         self._h = C.c_void_p()
+        ctx._guard_pools(k_pools[0])
         _check(lib().laps_graph_capture(ctx._h, arr, C.c_int32(len_bucket), C.c_int32(depth), C.c_int32(max_pages), kp, vp,
                                         C.c_void_p(stream.cuda_stream), C.byref(self._h)))
 

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
                                                         const int* __restrict__ page_table, int max_pages,
                                                         const int* __restrict__ tile_start,
                                                         const int* __restrict__ item_seq, int n_seq, int n_q,
-                                                        int n_kv, float scale_log2e) {
+                                                        int n_kv, float scale_log2e, int n_pool_pages) {
     constexpr int NTHR = NW * 64;
     constexpr int CPR = HD / 8;            // 16-byte chunks per K row
     constexpr int CPP = HD * 2;            // 16-byte chunks per page (K and V alike)
@@ -109,10 +109,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
     const int qtile = item - tile_start[seq];
     const int kvh = blockIdx.y;
     const int G = n_q / n_kv;
-    const int L = new_len[seq], H = prefix_len[seq];
+    const int L = new_len[seq], H = prefix_len[seq] > 0 ? prefix_len[seq] : 0;
     const int n_rows = L * G;
     const int kv_len = H + L;
-    const int n_pages_seq = (kv_len + LAPS_PAGE - 1) / LAPS_PAGE;
+    // never index past the table's width, whatever the lengths say (keys beyond it then repeat the last page)
+    const int n_pages_need = (kv_len + LAPS_PAGE - 1) / LAPS_PAGE;
+    const int n_pages_seq = n_pages_need < max_pages ? n_pages_need : max_pages;
     const int R0 = qtile * ROWS;
     if (R0 >= n_rows) return;
     const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
@@ -173,7 +175,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
             const int c = tid + i * NTHR;
             const int within = c % CPP;
             const int pg = pgn[i];
-            const size_t page = (size_t)(pg > 0 ? pg : 0);  // an unset (-1) entry must not turn into a wild address
+            // an unset (-1) entry or an id outside the pool must not turn into a wild address
+            const size_t page = (size_t)((pg > 0 && pg < n_pool_pages) ? pg : 0);
             const size_t off = ((page * n_kv + kvh) * CPP + within);
             kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
             vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];
@@ -371,7 +374,7 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     if (item >= tile_start[n_seq]) return;
     const int seq = item_seq[item], qtile = item - tile_start[seq], kvh = blockIdx.y;
     const int G = n_q / n_kv;
-    const int L = new_len[seq], H = prefix_len[seq];
+    const int L = new_len[seq], H = prefix_len[seq] > 0 ? prefix_len[seq] : 0;   // as in attn_kernel
     const int n_rows = L * G, R0 = qtile * ROWS;
     if (R0 >= n_rows) return;
     const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
@@ -436,11 +439,11 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
 template <int HD, int NW>
 int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool, const int* row_start,
                 const int* new_len, const int* prefix_len, const int* page_table, int max_pages, const int* tile_start,
-                const int* item_seq, int n_seq, int max_items, int n_q, int n_kv, hipStream_t s) {
+                const int* item_seq, int n_seq, int max_items, int n_q, int n_kv, int n_pool_pages, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
     hipLaunchKernelGGL((attn_kernel<HD, NW, false>), dim3(max_items, n_kv), dim3(NW * 64), 0, s, q, out, nullptr, nullptr,
                        k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
-                       n_q, n_kv, scale_log2e);
+                       n_q, n_kv, scale_log2e, n_pool_pages);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -449,14 +452,14 @@ template <int HD>
 int launch_attn_split(const bf16_t* q, bf16_t* out, float* part, const bf16_t* k_pool, const bf16_t* v_pool,
                       const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
                       int max_pages, const int* tile_start, const int* item_seq, int n_seq, int max_items, int n_split,
-                      int n_q, int n_kv, hipStream_t s) {
+                      int n_q, int n_kv, int n_pool_pages, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
     const size_t blocks = (size_t)max_items * n_kv * n_split;
     float* part_o = part;
     float* part_ml = part + blocks * 128 * HD;
     hipLaunchKernelGGL((attn_kernel<HD, 4, true>), dim3(max_items, n_kv, n_split), dim3(256), 0, s, q, out, part_o, part_ml,
                        k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
-                       n_q, n_kv, scale_log2e);
+                       n_q, n_kv, scale_log2e, n_pool_pages);
     LAPS_LAUNCH_CHECK();
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(max_items, n_kv, HD / 4), dim3(128 * MERGE_GROUPS), 0, s, out, part_o, part_ml,
                        row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split);
@@ -524,7 +527,7 @@ int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
                           int max_pages, int n_seq, int n_tokens, const int* tile_start, const int* item_seq,
-                          float* partial, int n_q, int n_kv, int hd, hipStream_t s) {
+                          float* partial, int n_q, int n_kv, int hd, int n_pool_pages, hipStream_t s) {
     int mt, max_items, n_split;
     attn_blocking(n_seq, n_tokens, n_q / n_kv, n_kv, max_pages, &mt, &max_items, &n_split);
     if (n_split > 1) {
@@ -532,16 +535,16 @@ int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, co
             laps_set_error("attention: key-split launch needs the partial-result workspace");
             return LAPS_EINVAL;
         }
-        if (hd == 128) return launch_attn_split<128>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, s);
-        if (hd == 64) return launch_attn_split<64>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, s);
+        if (hd == 128) return launch_attn_split<128>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, s);
+        if (hd == 64) return launch_attn_split<64>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, s);
     }
     if (hd == 128) {
-        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
+        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
     }
     if (hd == 64) {
-        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
-        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, s);
+        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
+        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
     }
     laps_set_error("attention: head_dim %d not supported (64 or 128)", hd);
     return LAPS_EINVAL;

@@ -1,6 +1,7 @@
 // C ABI of liblaps: context, workspace carving, the layer / stack driver, captured short-bucket
 // graphs, per-kernel event timing.  Every device step is a kernel from gemm.hip, elementwise.hip or
 // attention.hip; this file only sequences launches on the caller's stream.
+#include <climits>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -26,6 +27,7 @@ struct laps_ctx {
     laps_model_cfg cfg;
     int device;
     int max_pos;
+    int pool_pages;  // page ids must be below this (INT_MAX: unknown, not checked)
     float2* rope;  // [max_pos][hd/2] (cos, sin)
     // timing
     bool prof_on;
@@ -113,6 +115,7 @@ extern "C" int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions,
     }
     c->cfg = *cfg;
     c->max_pos = max_positions;
+    c->pool_pages = INT_MAX;
     c->rope = nullptr;
     c->prof_on = false;
     c->ev_used = 0;
@@ -142,6 +145,15 @@ extern "C" void laps_ctx_destroy(laps_ctx* c) {
     for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
     if (c->rope) (void)hipFree(c->rope);
     delete c;
+}
+
+extern "C" int laps_ctx_set_pool_pages(laps_ctx* c, int32_t n_pages) {
+    if (!c || n_pages < 0) {
+        laps_set_error("ctx_set_pool_pages: NULL context or negative page count");
+        return LAPS_EINVAL;
+    }
+    c->pool_pages = n_pages == 0 ? INT_MAX : n_pages;
+    return LAPS_OK;
 }
 
 extern "C" size_t laps_workspace_bytes(const laps_ctx* c, int32_t max_tokens, int32_t max_seqs) {
@@ -248,8 +260,8 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
 
     {
         ProfScope ps(c, s, LAPS_K_PREP, capturing);
-        LAPS_TRY(laps_launch_prep(M, b.n_seq, b.row_start, b.seq_len, b.prefix_len, b.page_table, b.max_pages, new_len,
-                                  tok_pos, tok_slot, s));
+        LAPS_TRY(laps_launch_prep(M, b.n_seq, b.row_start, b.seq_len, b.prefix_len, b.page_table, b.max_pages,
+                                  c->pool_pages, new_len, tok_pos, tok_slot, s));
     }
     {
         ProfScope ps(c, s, LAPS_K_PREP, capturing);
@@ -277,7 +289,8 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         {
             ProfScope ps(c, s, LAPS_K_ATTN, capturing);
             LAPS_TRY(laps_launch_attention(q, attn, kp, vp, b.row_start, new_len, b.prefix_len, b.page_table, b.max_pages,
-                                           b.n_seq, M, tile_start, item_seq, partial, cf.n_q_heads, cf.n_kv_heads, hd, s));
+                                           b.n_seq, M, tile_start, item_seq, partial, cf.n_q_heads, cf.n_kv_heads, hd,
+                                           c->pool_pages, s));
         }
         // x_mid = resid + attn W_o^T ; r = rmsnorm(x_mid; ln2)
         LAPS_TRY(run_gemm(c, LAPS_K_GEMM_O, capturing, attn, static_cast<const bf16_t*>(lw.w_o), M, d, qd, EPI_RESID,
@@ -404,7 +417,7 @@ static int kv_move(bool scatter, laps_ctx* c, int n_seq, int n_tokens, const int
     }
     return laps_launch_kv_move(scatter, n_seq, n_tokens, cu, start_pos, pt, max_pages, static_cast<bf16_t*>(k_tok),
                                static_cast<bf16_t*>(v_tok), static_cast<bf16_t*>(k_pool), static_cast<bf16_t*>(v_pool),
-                               c->cfg.n_kv_heads, c->cfg.head_dim, static_cast<hipStream_t>(stream));
+                               c->cfg.n_kv_heads, c->cfg.head_dim, c->pool_pages, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int laps_kv_scatter(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* start_pos,
@@ -477,7 +490,7 @@ extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
     unsigned char* w8 = static_cast<unsigned char*>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
     int* new_len = reinterpret_cast<int*>(w8 + L.new_len);
-    LAPS_TRY(laps_launch_prep(n_tokens, n_seq, cu, seq_len, prefix_len, pt, max_pages, new_len,
+    LAPS_TRY(laps_launch_prep(n_tokens, n_seq, cu, seq_len, prefix_len, pt, max_pages, c->pool_pages, new_len,
                               reinterpret_cast<int*>(w8 + L.tok_pos), reinterpret_cast<int*>(w8 + L.tok_slot), s));
     LAPS_TRY(laps_launch_attn_sched(new_len, n_seq, n_tokens, max_pages, reinterpret_cast<int*>(w8 + L.tile_start),
                                     reinterpret_cast<int*>(w8 + L.item_seq), c->cfg.n_q_heads, c->cfg.n_kv_heads, s));
@@ -485,7 +498,7 @@ extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
                                  static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), cu, new_len,
                                  prefix_len, pt, max_pages, n_seq, n_tokens, reinterpret_cast<int*>(w8 + L.tile_start),
                                  reinterpret_cast<int*>(w8 + L.item_seq), reinterpret_cast<float*>(w8 + L.partial), c->cfg.n_q_heads, c->cfg.n_kv_heads,
-                                 c->cfg.head_dim, s);
+                                 c->cfg.head_dim, c->pool_pages, s);
 }
 
 // ----------------------------------------------------------------------------- captured buckets

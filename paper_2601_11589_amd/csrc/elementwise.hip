@@ -36,7 +36,8 @@ __global__ void rope_table_kernel(float2* table, int max_pos, int half, double t
 // KV slot (page * 16 + offset) of the token; -1 for padding rows.
 __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_start, const int* __restrict__ seq_len,
                             const int* __restrict__ prefix_len, const int* __restrict__ page_table, int max_pages,
-                            int* __restrict__ new_len_out, int* __restrict__ tok_pos, int* __restrict__ tok_slot) {
+                            int n_pool_pages, int* __restrict__ new_len_out, int* __restrict__ tok_pos,
+                            int* __restrict__ tok_slot) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row < n_seq) {
         const int cap = row_start[row + 1] - row_start[row];
@@ -57,9 +58,12 @@ __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_s
     l = l > cap ? cap : l;
     int pos = -1, slot = -1;
     if (t >= 0 && t < l) {
-        pos = prefix_len[s] + t;
-        const int page = page_table[(size_t)s * max_pages + pos / LAPS_PAGE];
-        slot = page >= 0 ? page * LAPS_PAGE + pos % LAPS_PAGE : -1;  // unset table entry: treat as padding
+        const int h = prefix_len[s];
+        pos = (h > 0 ? h : 0) + t;
+        // a position past the table's width, an unset (-1) entry or a page id outside the pool: no cache write
+        const int pi = pos / LAPS_PAGE;
+        const int page = pi < max_pages ? page_table[(size_t)s * max_pages + pi] : -1;
+        slot = (page >= 0 && page < n_pool_pages) ? page * LAPS_PAGE + pos % LAPS_PAGE : -1;
     }
     tok_pos[row] = pos;
     tok_slot[row] = slot;
@@ -287,7 +291,7 @@ template <bool SCATTER>
 __global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ cu, const int* __restrict__ start_pos,
                                const int* __restrict__ page_table, int max_pages, bf16_t* __restrict__ k_tok,
                                bf16_t* __restrict__ v_tok, bf16_t* __restrict__ k_pool, bf16_t* __restrict__ v_pool,
-                               int n_kv, int hd) {
+                               int n_kv, int hd, int n_pool_pages) {
     const int tok = blockIdx.x;
     if (tok >= n_tokens) return;
     int lo = 0, hi = n_seq;
@@ -296,8 +300,9 @@ __global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ 
         if (cu[mid] <= tok) lo = mid; else hi = mid;
     }
     const int pos = start_pos[lo] + (tok - cu[lo]);
+    if (pos < 0 || pos / LAPS_PAGE >= max_pages) return;  // outside the table
     const int page = page_table[(size_t)lo * max_pages + pos / LAPS_PAGE], off = pos % LAPS_PAGE;
-    if (page < 0) return;  // unset table entry
+    if (page < 0 || page >= n_pool_pages) return;  // unset table entry, or not a page of the pool
     for (int i = threadIdx.x; i < n_kv * hd; i += blockDim.x) {
         const int g = i / hd, e = i % hd;
         const size_t kp = (((size_t)page * n_kv + g) * LAPS_PAGE + off) * hd + e;
@@ -382,11 +387,11 @@ int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta
 }
 
 int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq_len, const int* prefix_len,
-                     const int* page_table, int max_pages, int* new_len_out, int* tok_pos, int* tok_slot,
-                     hipStream_t s) {
+                     const int* page_table, int max_pages, int n_pool_pages, int* new_len_out, int* tok_pos,
+                     int* tok_slot, hipStream_t s) {
     const int n = n_rows > n_seq ? n_rows : n_seq;
     hipLaunchKernelGGL(prep_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n_rows, n_seq, row_start, seq_len,
-                       prefix_len, page_table, max_pages, new_len_out, tok_pos, tok_slot);
+                       prefix_len, page_table, max_pages, n_pool_pages, new_len_out, tok_pos, tok_slot);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -448,14 +453,14 @@ int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, in
 
 int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
                         const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
-                        bf16_t* v_pool, int n_kv, int hd, hipStream_t s) {
+                        bf16_t* v_pool, int n_kv, int hd, int n_pool_pages, hipStream_t s) {
     if (n_tokens == 0) return LAPS_OK;
     if (scatter)
         hipLaunchKernelGGL(kv_move_kernel<true>, dim3(n_tokens), dim3(256), 0, s, n_seq, n_tokens, cu, start_pos,
-                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd);
+                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd, n_pool_pages);
     else
         hipLaunchKernelGGL(kv_move_kernel<false>, dim3(n_tokens), dim3(256), 0, s, n_seq, n_tokens, cu, start_pos,
-                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd);
+                           page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd, n_pool_pages);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }

@@ -63,9 +63,11 @@ int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m,
 
 // ----------------------------------------------------------------------------- element-wise / epilogues
 int laps_launch_rope_table(float2* table, int max_pos, int head_dim, float theta, hipStream_t s);
+// n_pool_pages (here, in the K/V movers and in the attention): page ids outside [0, n_pool_pages) are treated as
+// unset entries - no cache write, no wild read.  INT_MAX when the caller has not said how many pages its pools hold.
 int laps_launch_prep(int n_rows, int n_seq, const int* row_start, const int* seq_len, const int* prefix_len,
-                     const int* page_table, int max_pages, int* new_len_out, int* tok_pos, int* tok_slot,
-                     hipStream_t s);
+                     const int* page_table, int max_pages, int n_pool_pages, int* new_len_out, int* tok_pos,
+                     int* tok_slot, hipStream_t s);
 // row_live (here and below): NULL, or one entry per row; rows with a negative entry are padding and are skipped.
 int laps_launch_rmsnorm(const float* x, const bf16_t* w, bf16_t* out, int rows, int d, float eps, const int* row_live,
                         hipStream_t s);
@@ -80,7 +82,7 @@ int laps_launch_epi_swiglu(const float* partial, int split, bf16_t* act, int row
 int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, int inter, int d, hipStream_t s);
 int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
                         const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
-                        bf16_t* v_pool, int n_kv, int hd, hipStream_t s);
+                        bf16_t* v_pool, int n_kv, int hd, int n_pool_pages, hipStream_t s);
 // Graph staging: clamped lengths / prefixes of `depth` slots (the first n_real from the caller's device arrays, the
 // rest empty) and packed row offsets row_start_out[depth + 1].
 int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
@@ -99,4 +101,4 @@ int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
                           const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
                           int max_pages, int n_seq, int n_tokens, const int* tile_start, const int* item_seq,
-                          float* partial, int n_q, int n_kv, int hd, hipStream_t s);
+                          float* partial, int n_q, int n_kv, int hd, int n_pool_pages, hipStream_t s);

@@ -45,6 +45,9 @@ def stage_short_batches(plan: dict, new_len, prefix_len, page_table, cu, d_x: to
                          device="cuda")
         out.append(StagedBatch(lb, b["depth"], b["graph_ok"], ids, n_real, sl, pl, pt, x, c,
                                int(sum(int(new_len[i]) for i in ids))))
+    # the tensors were filled on torch's current stream; the runner launches on a stream of its own, which does not
+    # wait for that one by itself
+    torch.cuda.current_stream().synchronize()
     return out
 
 
