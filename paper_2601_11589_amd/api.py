@@ -325,6 +325,9 @@ class LapsCtx:
         if need == 0:
             raise LapsError("laps_workspace_bytes returned 0 (bad arguments)")
         if self._ws is None or self._ws.numel() < need:
+            # kernels launched through the library on other streams may still use the old buffer, and torch's allocator
+            # knows nothing of them: let them finish before the block goes back to it
+            torch.cuda.synchronize()
             self._ws = None
             self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
         return self._ws
