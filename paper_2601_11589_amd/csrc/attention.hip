@@ -77,6 +77,14 @@ __device__ __forceinline__ void split_geometry(int kv_end, int n_split, int* eff
     *per = (nt + e - 1) / e;
 }
 
+// A prefix length that the page table cannot hold (a corrupted or stale array) must neither index past the
+// table nor make a workgroup walk millions of key tiles: cut to what max_pages pages can address.
+__device__ __forceinline__ int clamp_prefix(int h, int new_len, int max_pages) {
+    const int room = max_pages * LAPS_PAGE - new_len;
+    h = h < room ? h : room;
+    return h > 0 ? h : 0;
+}
+
 // Two waves per SIMD in every variant (second launch-bound argument): with 4 waves per workgroup that is two
 // resident workgroups per compute unit, which the key-streaming launches need to cover the memory latency.
 template <int HD, int NW, bool SPLIT>
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
     const int qtile = item - tile_start[seq];
     const int kvh = blockIdx.y;
     const int G = n_q / n_kv;
-    const int L = new_len[seq], H = prefix_len[seq] > 0 ? prefix_len[seq] : 0;
+    const int L = new_len[seq], H = clamp_prefix(prefix_len[seq], L, max_pages);
     const int n_rows = L * G;
     const int kv_len = H + L;
     // never index past the table's width, whatever the lengths say (keys beyond it then repeat the last page)
@@ -365,7 +373,8 @@ template <int HD>
 __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     bf16_t* __restrict__ out, const float* __restrict__ part_o, const float* __restrict__ part_ml,
     const int* __restrict__ row_start, const int* __restrict__ new_len, const int* __restrict__ prefix_len,
-    const int* __restrict__ tile_start, const int* __restrict__ item_seq, int n_seq, int n_q, int n_kv, int n_split) {
+    const int* __restrict__ tile_start, const int* __restrict__ item_seq, int n_seq, int n_q, int n_kv, int n_split,
+    int max_pages) {
     constexpr int ROWS = 128;
     __shared__ float red_m[MERGE_GROUPS][ROWS];
     __shared__ float red_l[MERGE_GROUPS][ROWS];
@@ -374,7 +383,7 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     if (item >= tile_start[n_seq]) return;
     const int seq = item_seq[item], qtile = item - tile_start[seq], kvh = blockIdx.y;
     const int G = n_q / n_kv;
-    const int L = new_len[seq], H = prefix_len[seq] > 0 ? prefix_len[seq] : 0;   // as in attn_kernel
+    const int L = new_len[seq], H = clamp_prefix(prefix_len[seq], L, max_pages);   // as in attn_kernel
     const int n_rows = L * G, R0 = qtile * ROWS;
     if (R0 >= n_rows) return;
     const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
@@ -462,7 +471,7 @@ int launch_attn_split(const bf16_t* q, bf16_t* out, float* part, const bf16_t* k
                        n_q, n_kv, scale_log2e, n_pool_pages);
     LAPS_LAUNCH_CHECK();
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(max_items, n_kv, HD / 4), dim3(128 * MERGE_GROUPS), 0, s, out, part_o, part_ml,
-                       row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split);
+                       row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split, max_pages);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
