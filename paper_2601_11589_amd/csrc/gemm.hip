@@ -364,9 +364,10 @@ GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
         return p;
     };
     if (m <= 128) {
-        // Bandwidth-bound.  The L2 -> CU path carries W once plus the A slab once per workgroup per
-        // K step, and saturates near 9 TB/s in aggregate: a 256-column tile halves the A share of a
-        // 128-column one, which decides the wide projections (gate/up: 5.3 against 4.4 TB/s).  A narrow
+        // Bandwidth-bound.  A CU keeps a bounded number of requests in flight, and the A slab that every
+        // workgroup re-reads per K step (L2 hits) takes its share of them from the weight stream: a
+        // 256-column tile halves the A share of a 128-column one, which decides the wide projections
+        // (gate/up: 5.3 against 4.4 TB/s of weights).  A narrow
         // projection (q/k/v, o: 20-28 tiles of 256 columns) never gets near that limit; it pays for the
         // K split that has to fill the chip - every slice writes m*n fp32 partial sums that a reduce
         // kernel reads back - and for the short pipeline of each slice.  128-column tiles need half the
