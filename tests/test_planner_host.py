@@ -98,6 +98,21 @@ def test_library_exports_every_declared_symbol(repo_root):
     assert lib.laps_version().decode().startswith("laps-gfx950")
 
 
+def test_null_handles_are_rejected_without_touching_the_gpu():
+    """Entry points that take a context or a graph return LAPS_EINVAL (-1) on a NULL handle before any HIP call."""
+    import ctypes as C
+    lib = api.lib()
+    assert lib.laps_ctx_set_pool_pages(None, C.c_int32(8)) == -1
+    assert b"pool_pages" in lib.laps_last_error()
+    assert lib.laps_prof_enable(None, C.c_int32(1)) == -1
+    assert lib.laps_graph_replay(None, None) == -1
+    assert lib.laps_graph_stage(None, C.c_int32(0), None, None, None, None, C.c_int32(0), None) == -1
+    assert lib.laps_workspace_bytes(None, C.c_int32(8), C.c_int32(1)) == 0
+    assert lib.laps_graph_device_bytes(None) == 0
+    lib.laps_graph_destroy(None)
+    lib.laps_ctx_destroy(None)
+
+
 def test_planner_under_address_and_ub_sanitizers(repo_root, tmp_path):
     """Host code only: the planner and a random-input driver built with -fsanitize=address,undefined."""
     exe = str(tmp_path / "planner_san")
