@@ -513,6 +513,8 @@ def main():
     ap.add_argument("--no-reprefill", action="store_true", help="skip the multi-turn re-prefill workload (configs[2])")
     ap.add_argument("--no-graph-cost", action="store_true", help="skip the graph capture cost table (7B/14B/32B shapes)")
     ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
+    ap.add_argument("--budget-sweep", type=str, default="256,512,1024",
+                    help="further token budgets for the short workload (tokens/s against latency); empty = none")
     ap.add_argument("--no-two-streams", action="store_true",
                     help="short buckets: skip the variant that alternates the replays between two streams")
     ap.add_argument("--loads", type=str, default="0.7",
@@ -578,6 +580,14 @@ def main():
         tm["gemm_TFLOPs"] = gm["TFLOPs"]
         tm["gemm_frac_of_mfma_peak"] = gm["TFLOPs"] / MFMA_BF16_PEAK_TFS
         line["short_token_max"] = tm
+    if not args.no_token_max and args.budget_sweep:
+        # the same short workload at token budgets between the latency-oriented default and token-max
+        log("[bench] leg: short buckets, token budget sweep")
+        sweep = {}
+        for tb in (int(x) for x in args.budget_sweep.split(",")):
+            r = run_short(ctx, layers, cfg, tb, max(2, args.steps // 2), 1, False, f"budget-{tb}")
+            sweep[str(tb)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "n_batches", "latency_ms_p50", "latency_ms_p90")}
+        line["short_budget_sweep"] = sweep
     if not args.no_reprefill:
         # configs[2]: multi-turn re-prefill, 128 requests of U[16,64] new tokens over U[512,4096] cached tokens
         log("[bench] leg: re-prefill (configs[2])")
