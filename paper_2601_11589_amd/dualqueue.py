@@ -68,16 +68,26 @@ class DualQueue:
     """Holds the device-resident workload (packed activations, page tables, pools) and runs either policy."""
 
     def __init__(self, ctx: api.LapsCtx, layers, new_len, prefix_len, page_table, d_x: torch.Tensor, k_pools, v_pools,
-                 params: DQParams, keep_outputs: bool = False):
+                 params: DQParams, keep_outputs: bool = False, step_model=None):
+        """step_model: None runs every step on the GPU.  Otherwise an object with
+        `varlen_us(segs)` (segs = [(request, first new token, count, cached tokens before it)]) and
+        `graph_us(len_bucket, depth, new_lens)` that returns the duration of a step instead of running it: the
+        policies below then work on the clock alone (no GPU, no device memory; ctx, layers, page_table, d_x and the
+        pools may be None) - for tests of the step loops against queueing theory and for what-if studies."""
         self.ctx, self.layers, self.p = ctx, layers, params
         self.new_len = np.asarray(new_len, np.int64)
         self.prefix_len = np.asarray(prefix_len, np.int64)
-        self.page_table = np.ascontiguousarray(page_table, np.int32)
-        self.d_page_table = torch.from_numpy(self.page_table).cuda()
-        self.cu = np.concatenate([[0], np.cumsum(self.new_len)])
-        self.d_x, self.k_pools, self.v_pools = d_x, k_pools, v_pools
         self.n = len(self.new_len)
         self.is_long = self.new_len > params.short_max_len
+        self.cu = np.concatenate([[0], np.cumsum(self.new_len)])
+        self.step_model = step_model
+        self.out = None
+        if step_model is not None:
+            self.short = None
+            return
+        self.page_table = np.ascontiguousarray(page_table, np.int32)
+        self.d_page_table = torch.from_numpy(self.page_table).cuda()
+        self.d_x, self.k_pools, self.v_pools = d_x, k_pools, v_pools
         self.stream = torch.cuda.Stream()
         self.short = runner.ShortRunner(ctx, layers, k_pools, v_pools, self.page_table.shape[1], self.stream)
         self.out = torch.zeros_like(d_x) if keep_outputs else None
@@ -95,6 +105,8 @@ class DualQueue:
 
     def _run_varlen(self, segs) -> float:
         """segs: list of (request, first new token, count).  One un-captured packed batch."""
+        if self.step_model is not None:
+            return float(self.step_model.varlen_us([(r, a, c, int(self.prefix_len[r]) + a) for r, a, c in segs]))
         with torch.cuda.stream(self.stream):
             ids = [s[0] for s in segs]
             x = torch.cat([self.d_x[self.cu[r] + a: self.cu[r] + a + c] for r, a, c in segs])
@@ -129,6 +141,10 @@ class DualQueue:
 
     def _run_planned(self, ids, plan):
         """Replays one captured graph per batch of `plan` (request ids local to `ids`)."""
+        if self.step_model is not None:
+            return [([ids[j] for j in b["req_ids"]],
+                     float(self.step_model.graph_us(b["len_bucket"], b["depth"], [int(self.new_len[ids[j]]) for j in b["req_ids"]])))
+                    for b in plan["batches"]]
         cu_local = np.concatenate([[0], np.cumsum(self.new_len[ids])])
         with torch.cuda.stream(self.stream):
             x_local = torch.cat([self.d_x[self.cu[r]: self.cu[r + 1]] for r in ids])
@@ -314,4 +330,5 @@ class DualQueue:
         return DQResult(mode, t, busy, kinds["short_graph"] + kinds["long_chunk"], finish, finish - arrival, kinds)
 
     def close(self):
-        self.short.close()
+        if self.short is not None:
+            self.short.close()
