@@ -185,6 +185,21 @@ int laps_prefill_stack(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq
                        const float* x_in_dev, float* x_out_dev, void* workspace_dev, size_t workspace_bytes,
                        void* stream);
 
+/* ------------------------------------------------------------------ launch plans (host only, no device work)
+ * What the library would launch for a shape; for tests of the launch arithmetic and for tuning.
+ * laps_gemm_plan_info: the projection C[m,n] = A[m,k] W[n,k]^T with the epilogue the layer driver would ask for
+ * (0 = K-slice partial sums, 1 = residual add, 2 = SwiGLU) and split_k as in laps_gemm_bf16 (0 = automatic).
+ * out[7] = { tile rows, tile columns, K slices, K elements per slice, epilogue the kernel applies (0 when K is
+ * split), slabs kept in flight per workgroup, workgroups }.
+ * laps_attn_plan_info: the attention launch of a batch shape (n_tokens rows, n_seq sequences, page tables
+ * max_pages wide).  out[6] = { query rows per workgroup, bound on the (sequence, row block) work items,
+ * key-range splits (1 = none), fewest 64-key tiles a split is given, bytes of the work-item table, bytes of
+ * the key-split partial results (0 if tables this narrow never split) }.
+ * EINVAL on NULL or unsupported shapes. */
+int laps_gemm_plan_info(int32_t m, int32_t n, int32_t k, int32_t split_k, int32_t epilogue, int32_t* out);
+int laps_attn_plan_info(int32_t n_seq, int32_t n_tokens, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                        int32_t max_pages, int64_t* out);
+
 /* ------------------------------------------------------------------ captured short buckets
  * Section 3.1: one graph per (length bucket L_b, depth B_d) with fixed operator topology and
  * variable memory contents.  The graph runs the whole stack on up to depth sequences of up to

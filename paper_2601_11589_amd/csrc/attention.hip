@@ -518,6 +518,14 @@ static void attn_blocking(int n_seq, int n_tokens, int group, int n_kv, int max_
     *max_items = (int)(total_rows / rows_per_wg) + n_seq;
 }
 
+void laps_attn_plan(int n_seq, int n_tokens, int group, int n_kv, int max_pages, int* rows_per_wg, int* max_items,
+                    int* n_split, int* min_tiles_per_split) {
+    int mt = 1;
+    attn_blocking(n_seq, n_tokens, group, n_kv, max_pages, &mt, max_items, n_split);
+    *rows_per_wg = 128 * mt;
+    *min_tiles_per_split = MIN_TILES_PER_SPLIT;
+}
+
 // Work-item table for laps_launch_attention; depends on the batch only, so a layer stack builds it once.
 size_t laps_attn_item_table_bytes(int max_tokens, int max_seqs, int group) {
     return ((size_t)max_tokens * group / 128 + max_seqs + 1) * sizeof(int);

@@ -501,6 +501,47 @@ extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, cons
                                  c->cfg.head_dim, c->pool_pages, s);
 }
 
+// ----------------------------------------------------------------------------- launch plans (host only)
+extern "C" int laps_gemm_plan_info(int32_t m, int32_t n, int32_t k, int32_t split_k, int32_t epilogue, int32_t* out) {
+    if (!out || m < 1 || n < 64 || n % 64 || k < 64 || k % 64 || split_k < 0 || epilogue < 0 || epilogue > 2) {
+        laps_set_error("gemm_plan_info: NULL output or unsupported shape (m=%d n=%d k=%d)", m, n, k);
+        return LAPS_EINVAL;
+    }
+    const GemmPlan p = laps_gemm_plan(m, n, k, split_k, epilogue);
+    int bm = 0, bn = 0;
+    laps_gemm_tile_dims(p.cfg, &bm, &bn);
+    if (bm == 0 || n % bn != 0) {
+        laps_set_error("gemm_plan_info: no tile shape divides n=%d", n);
+        return LAPS_EINVAL;
+    }
+    out[0] = bm;
+    out[1] = bn;
+    out[2] = p.split;
+    out[3] = p.k_per_split;
+    out[4] = p.epi;
+    out[5] = p.ws;
+    out[6] = ((m + bm - 1) / bm) * (n / bn) * p.split;
+    return LAPS_OK;
+}
+
+extern "C" int laps_attn_plan_info(int32_t n_seq, int32_t n_tokens, int32_t n_q_heads, int32_t n_kv_heads,
+                                   int32_t head_dim, int32_t max_pages, int64_t* out) {
+    if (!out || n_seq < 1 || n_tokens < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads ||
+        (head_dim != 64 && head_dim != 128) || max_pages < 1) {
+        laps_set_error("attn_plan_info: NULL output or unsupported shape");
+        return LAPS_EINVAL;
+    }
+    int rows = 0, items = 0, split = 0, min_tiles = 0;
+    laps_attn_plan(n_seq, n_tokens, n_q_heads / n_kv_heads, n_kv_heads, max_pages, &rows, &items, &split, &min_tiles);
+    out[0] = rows;
+    out[1] = items;
+    out[2] = split;
+    out[3] = min_tiles;
+    out[4] = (int64_t)laps_attn_item_table_bytes(n_tokens, n_seq, n_q_heads / n_kv_heads);
+    out[5] = (int64_t)laps_attn_partial_bytes(head_dim, max_pages);
+    return LAPS_OK;
+}
+
 // ----------------------------------------------------------------------------- captured buckets
 struct laps_graph {
     laps_ctx* ctx;

@@ -343,6 +343,11 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 }  // namespace
 
+void laps_gemm_tile_dims(int cfg, int* bm, int* bn) {
+    *bm = (cfg >= 0 && cfg < kNumTiles) ? kTiles[cfg].bm : 0;
+    *bn = (cfg >= 0 && cfg < kNumTiles) ? kTiles[cfg].bn : 0;
+}
+
 // Picks tile shape and K split.
 GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi) {
     GemmPlan p;

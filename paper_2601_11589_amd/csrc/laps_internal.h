@@ -56,6 +56,7 @@ struct GemmPlan {
 };
 GemmPlan laps_gemm_plan(int m, int n, int k, int force_split, int want_epi);
 size_t laps_gemm_partial_bytes(int m, int n, int k);
+void laps_gemm_tile_dims(int cfg, int* bm, int* bn);   // rows and columns of tile shape `cfg` (0, 0 if unknown)
 // row_live: NULL, or m entries; a negative entry marks a padding row.  Output rows of padding are unspecified:
 // the skinny tiles do not load them (they compute with zeros), and a row tile of padding only is skipped.
 int laps_gemm_launch(const GemmPlan& p, const bf16_t* a, const bf16_t* w, int m, int n, int k, float* out_f32,
@@ -96,6 +97,10 @@ int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fil
 // tile_start: n_seq + 1 ints; item_seq: laps_attn_item_table_bytes (sequence of every row-block work item).
 size_t laps_attn_partial_bytes(int hd, int max_pages);   // 0 when page tables this narrow never split
 size_t laps_attn_item_table_bytes(int max_tokens, int max_seqs, int group);
+// The blocking laps_launch_attn_sched / laps_launch_attention derive from a launch shape: query rows per workgroup,
+// bound on the (sequence, row block) items, key-range splits (1 = none), fewest key tiles a split may get.
+void laps_attn_plan(int n_seq, int n_tokens, int group, int n_kv, int max_pages, int* rows_per_wg, int* max_items,
+                    int* n_split, int* min_tiles_per_split);
 int laps_launch_attn_sched(const int* new_len, int n_seq, int n_tokens, int max_pages, int* tile_start, int* item_seq,
                            int n_q, int n_kv, hipStream_t s);
 int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool,
