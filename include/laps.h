@@ -142,6 +142,9 @@ int laps_ctx_set_pool_pages(laps_ctx* ctx, int32_t n_pages);
 /* Bytes of scratch laps_prefill_layer / laps_prefill_stack need for up to max_tokens rows
  * (padded rows count) and max_seqs sequences.  0 on bad arguments. */
 size_t laps_workspace_bytes(const laps_ctx* ctx, int32_t max_tokens, int32_t max_seqs);
+/* The same figure from a model shape alone (host only; 0 on an unsupported shape).  A workspace of this size serves
+ * every call with at most max_tokens rows and max_seqs sequences. */
+size_t laps_workspace_bytes_for(const laps_model_cfg* cfg, int32_t max_tokens, int32_t max_seqs);
 
 /* Interleaves gate and up projection rows in blocks of 32 so that one GEMM produces both
  * halves of the SwiGLU for the same output column in one tile: dst rows [64b, 64b+32) are

@@ -52,6 +52,7 @@ def lib():
         L.laps_last_error.restype = C.c_char_p
         L.laps_version.restype = C.c_char_p
         L.laps_workspace_bytes.restype = C.c_size_t
+        L.laps_workspace_bytes_for.restype = C.c_size_t
         L.laps_gemm_workspace_bytes.restype = C.c_size_t
         L.laps_graph_device_bytes.restype = C.c_size_t
         L.laps_graph_output.restype = C.c_void_p

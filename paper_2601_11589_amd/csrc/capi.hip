@@ -147,6 +147,11 @@ extern "C" void laps_ctx_destroy(laps_ctx* c) {
     delete c;
 }
 
+extern "C" size_t laps_workspace_bytes_for(const laps_model_cfg* cfg, int32_t max_tokens, int32_t max_seqs) {
+    if (!check_cfg(cfg) || max_tokens < 1 || max_seqs < 1) return 0;
+    return ws_layout(*cfg, max_tokens, max_seqs).total;
+}
+
 extern "C" int laps_ctx_set_pool_pages(laps_ctx* c, int32_t n_pages) {
     if (!c || n_pages < 0) {
         laps_set_error("ctx_set_pool_pages: NULL context or negative page count");

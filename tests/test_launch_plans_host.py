@@ -133,3 +133,22 @@ def test_attention_tables_and_partials_hold_every_work_item_of_a_batch_shape():
                 assert ranges[0][0] == 0 and ranges[-1][1] == kv_end and all(a < b for a, b in ranges)
                 assert all(ranges[i][1] == ranges[i + 1][0] for i in range(len(ranges) - 1))
     assert seen_split > 200 and seen_flat > 200
+
+
+def test_a_workspace_sized_for_a_maximum_serves_every_smaller_batch():
+    """laps_workspace_bytes(max_tokens, max_seqs) must cover every call with fewer rows and sequences (each call
+    checks its own need against the buffer it is given): the K-split factor, and with it the partial-sum region,
+    does not grow monotonically with the row count."""
+    from paper_2601_11589_amd import inputs
+    lib = api.lib()
+    for cfgf in (inputs.tiny_cfg, inputs.qwen7b_cfg, inputs.qwen14b_cfg, inputs.qwen32b_cfg):
+        cfg = cfgf(1)
+        c = api._ModelCfg(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.intermediate, cfg.n_layers, 16,
+                          int(getattr(cfg, "has_qkv_bias", 0)), 1e6, 1e-6)
+        need = lambda m, s: lib.laps_workspace_bytes_for(C.byref(c), C.c_int32(m), C.c_int32(s))
+        assert need(0, 1) == 0 and need(8, 0) == 0
+        for cap, seqs in ((64, 4), (128, 8), (200, 8), (300, 16), (512, 8), (1000, 64), (2048, 1), (4096, 64)):
+            total = need(cap, seqs)
+            assert total > 0
+            for m in sorted(set(list(range(1, min(cap, 300) + 1)) + list(range(300, cap + 1, 37)) + [cap])):
+                assert need(m, min(seqs, m)) <= total, (cfgf.__name__, cap, m)
