@@ -668,7 +668,7 @@ extern "C" int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* se
     hipStream_t s = static_cast<hipStream_t>(stream);
     LAPS_TRY(laps_launch_stage_meta(seq_len, prefix_len, n_real, g->depth, g->len_bucket, g->seq_len, g->prefix_len,
                                     g->row_start, s));
-    LAPS_TRY(laps_launch_copy_i32(g->page_table, page_table, n_real * g->max_pages, 0, 0, g->depth * g->max_pages, s));
+    LAPS_TRY(laps_launch_copy_i32(g->page_table, page_table, n_real * g->max_pages, 0, g->depth * g->max_pages, s));
     if (n_rows > 0)
         LAPS_HIP(hipMemcpyAsync(g->x_in, x_rows, (size_t)n_rows * g->ctx->cfg.hidden * 4, hipMemcpyDeviceToDevice, s));
     return LAPS_OK;

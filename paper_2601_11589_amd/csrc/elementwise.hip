@@ -318,8 +318,8 @@ __global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ 
     }
 }
 
-// dst[i] = src[i] for i < n; dst[i] = fill_value for fill_from <= i < total (used to stage graph
-// metadata without memset nodes)
+// dst[i] = src[i] for i < n; dst[i] = fill_value for n <= i < total (stages a graph's page table without
+// memset nodes)
 __global__ void copy_fill_i32_kernel(int* __restrict__ dst, const int* __restrict__ src, int n, int fill_value, int total) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
@@ -465,8 +465,7 @@ int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, co
     return LAPS_OK;
 }
 
-int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s) {
-    (void)fill_from;
+int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_value, int total, hipStream_t s) {
     if (total <= 0) return LAPS_OK;
     hipLaunchKernelGGL(copy_fill_i32_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dst, src, n, fill_value, total);
     LAPS_LAUNCH_CHECK();

@@ -88,7 +88,8 @@ int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, co
 // rest empty) and packed row offsets row_start_out[depth + 1].
 int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
                            int* seq_len_out, int* prefix_out, int* row_start_out, hipStream_t s);
-int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_from, int fill_value, int total, hipStream_t s);
+// dst[i] = src[i] for i < n, fill_value for n <= i < total
+int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_value, int total, hipStream_t s);
 
 // ----------------------------------------------------------------------------- attention
 // Both take the same (n_seq, n_tokens, max_pages): the blocking they derive from them must agree.
