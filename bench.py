@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the ragged-prefill hot path on one MI355X.
 
-Primary workload (benchmark configs[1]): 256 new prompts, lengths U[8,64], bucketed to
-{16,32,64}, 4-layer stack of 32B-shaped layers, every bucket batch replayed as a captured
-hipGraph.  One "step" = plan + stage + replay of every batch of the 256 requests.
-Also reported in the same JSON line: the long-prefill workload (configs[3]) as `long_prefill`,
-the token-max variant of the short workload as `short_token_max`, and the fp64 oracle timed on
-the host cores as `cpu_baseline`.
+Primary workload (the short-prefill bucket configuration, configs[1] of the benchmark definition): 256 new
+prompts, lengths U[8,64], bucketed to {16,32,64}, 4-layer stack of 32B-shaped layers, every bucket batch replayed
+as a captured hipGraph.  One "step" = plan + stage + replay of every batch of the 256 requests.
+Also reported in the same JSON line: the same workload at larger token budgets (`short_budget_sweep`,
+`short_token_max`) and on two streams, the multi-turn re-prefill workload (`reprefill`), the long-prefill workload
+(`long_prefill`), the latency-model fit, the graph cost table, the simulated instance pools, the mixed dual-queue
+workload (`dual_queue`), and the fp64 oracle timed on the host cores (`cpu_baseline`).
 """
 from __future__ import annotations
 
