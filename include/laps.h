@@ -26,7 +26,11 @@
  *     returns: keep those arrays valid and unchanged until that stream work has completed.
  *     Arrays written by work on another stream must be complete before the call (event or
  *     synchronisation on the caller's side): a page table read before it is written makes the
- *     K/V append write wherever the stale entries point.  Page ids are not range-checked.
+ *     K/V append write wherever the stale entries point.  The kernels bound what the VALUES of these
+ *     arrays can reach: lengths are cut to the rows a sequence owns, a sequence whose rows do not
+ *     lie inside the batch is skipped, a prefix longer than the page table can address is cut to
+ *     it, and - once laps_ctx_set_pool_pages has said how many pages the pools hold - page ids
+ *     outside the pools are treated as unset.  The array SIZES are the caller's responsibility.
  *   - bf16 = upper 16 bits of an IEEE float32, round-to-nearest-even on conversion.
  *   - Layer math (all accumulation fp32): r = rmsnorm(x; ln1); [q,k,v] = r W_qkv^T (+b);
  *     rotate-half RoPE with theta on q,k at absolute position prefix_len+t; causal grouped-

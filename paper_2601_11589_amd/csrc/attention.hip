@@ -98,7 +98,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
                                                         const int* __restrict__ page_table, int max_pages,
                                                         const int* __restrict__ tile_start,
                                                         const int* __restrict__ item_seq, int n_seq, int n_q,
-                                                        int n_kv, float scale_log2e, int n_pool_pages) {
+                                                        int n_kv, float scale_log2e, int n_pool_pages, int n_tokens) {
     constexpr int NTHR = NW * 64;
     constexpr int CPR = HD / 8;            // 16-byte chunks per K row
     constexpr int CPP = HD * 2;            // 16-byte chunks per page (K and V alike)
@@ -118,6 +118,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
     const int kvh = blockIdx.y;
     const int G = n_q / n_kv;
     const int L = new_len[seq], H = clamp_prefix(prefix_len[seq], L, max_pages);
+    // row offsets come from the caller's device array: rows outside the batch are never touched, whatever it holds
+    const int rs = row_start[seq];
+    if (rs < 0 || L > n_tokens - rs) return;
     const int n_rows = L * G;
     const int kv_len = H + L;
     // never index past the table's width, whatever the lengths say (keys beyond it then repeat the last page)
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
         kv_end = (z + 1) * per * KT < kv_end_all ? (z + 1) * per * KT : kv_end_all;
     }
     const int* pt = page_table + (size_t)seq * max_pages;
-    const size_t tok0 = (size_t)row_start[seq];
+    const size_t tok0 = (size_t)rs;
     const int q_stride = n_q * HD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -374,7 +377,7 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     bf16_t* __restrict__ out, const float* __restrict__ part_o, const float* __restrict__ part_ml,
     const int* __restrict__ row_start, const int* __restrict__ new_len, const int* __restrict__ prefix_len,
     const int* __restrict__ tile_start, const int* __restrict__ item_seq, int n_seq, int n_q, int n_kv, int n_split,
-    int max_pages) {
+    int max_pages, int n_tokens) {
     constexpr int ROWS = 128;
     __shared__ float red_m[MERGE_GROUPS][ROWS];
     __shared__ float red_l[MERGE_GROUPS][ROWS];
@@ -384,6 +387,8 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     const int seq = item_seq[item], qtile = item - tile_start[seq], kvh = blockIdx.y;
     const int G = n_q / n_kv;
     const int L = new_len[seq], H = clamp_prefix(prefix_len[seq], L, max_pages);   // as in attn_kernel
+    const int rs = row_start[seq];
+    if (rs < 0 || L > n_tokens - rs) return;                                          // as in attn_kernel
     const int n_rows = L * G, R0 = qtile * ROWS;
     if (R0 >= n_rows) return;
     const int last_row_wg = (R0 + ROWS < n_rows ? R0 + ROWS : n_rows) - 1;
@@ -438,7 +443,7 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
     }
     const float inv = 1.f / l_all;
     const int tq = row_id / G, gq = row_id - tq * G;
-    bf16_t* op = out + ((size_t)row_start[seq] + tq) * (size_t)(n_q * HD) + (size_t)(kvh * G + gq) * HD;
+    bf16_t* op = out + ((size_t)rs + tq) * (size_t)(n_q * HD) + (size_t)(kvh * G + gq) * HD;
     u32x2 o2;
     o2.x = pack_bf16x2(o4.x * inv, o4.y * inv);
     o2.y = pack_bf16x2(o4.z * inv, o4.w * inv);
@@ -448,11 +453,12 @@ __global__ __launch_bounds__(128 * MERGE_GROUPS) void attn_merge_kernel(
 template <int HD, int NW>
 int launch_attn(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, const bf16_t* v_pool, const int* row_start,
                 const int* new_len, const int* prefix_len, const int* page_table, int max_pages, const int* tile_start,
-                const int* item_seq, int n_seq, int max_items, int n_q, int n_kv, int n_pool_pages, hipStream_t s) {
+                const int* item_seq, int n_seq, int max_items, int n_q, int n_kv, int n_pool_pages, int n_tokens,
+                hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
     hipLaunchKernelGGL((attn_kernel<HD, NW, false>), dim3(max_items, n_kv), dim3(NW * 64), 0, s, q, out, nullptr, nullptr,
                        k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
-                       n_q, n_kv, scale_log2e, n_pool_pages);
+                       n_q, n_kv, scale_log2e, n_pool_pages, n_tokens);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -461,17 +467,17 @@ template <int HD>
 int launch_attn_split(const bf16_t* q, bf16_t* out, float* part, const bf16_t* k_pool, const bf16_t* v_pool,
                       const int* row_start, const int* new_len, const int* prefix_len, const int* page_table,
                       int max_pages, const int* tile_start, const int* item_seq, int n_seq, int max_items, int n_split,
-                      int n_q, int n_kv, int n_pool_pages, hipStream_t s) {
+                      int n_q, int n_kv, int n_pool_pages, int n_tokens, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
     const size_t blocks = (size_t)max_items * n_kv * n_split;
     float* part_o = part;
     float* part_ml = part + blocks * 128 * HD;
     hipLaunchKernelGGL((attn_kernel<HD, 4, true>), dim3(max_items, n_kv, n_split), dim3(256), 0, s, q, out, part_o, part_ml,
                        k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq,
-                       n_q, n_kv, scale_log2e, n_pool_pages);
+                       n_q, n_kv, scale_log2e, n_pool_pages, n_tokens);
     LAPS_LAUNCH_CHECK();
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(max_items, n_kv, HD / 4), dim3(128 * MERGE_GROUPS), 0, s, out, part_o, part_ml,
-                       row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split, max_pages);
+                       row_start, new_len, prefix_len, tile_start, item_seq, n_seq, n_q, n_kv, n_split, max_pages, n_tokens);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -552,16 +558,16 @@ int laps_launch_attention(const bf16_t* q, bf16_t* out, const bf16_t* k_pool, co
             laps_set_error("attention: key-split launch needs the partial-result workspace");
             return LAPS_EINVAL;
         }
-        if (hd == 128) return launch_attn_split<128>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, s);
-        if (hd == 64) return launch_attn_split<64>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, s);
+        if (hd == 128) return launch_attn_split<128>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, n_tokens, s);
+        if (hd == 64) return launch_attn_split<64>(q, out, partial, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_split, n_q, n_kv, n_pool_pages, n_tokens, s);
     }
     if (hd == 128) {
-        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
-        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
+        if (mt == 2) return launch_attn<128, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, n_tokens, s);
+        return launch_attn<128, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, n_tokens, s);
     }
     if (hd == 64) {
-        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
-        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, s);
+        if (mt == 2) return launch_attn<64, 8>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, n_tokens, s);
+        return launch_attn<64, 4>(q, out, k_pool, v_pool, row_start, new_len, prefix_len, page_table, max_pages, tile_start, item_seq, n_seq, max_items, n_q, n_kv, n_pool_pages, n_tokens, s);
     }
     laps_set_error("attention: head_dim %d not supported (64 or 128)", hd);
     return LAPS_EINVAL;
