@@ -72,6 +72,16 @@ extern "C" int laps_ctrl_step(laps_ctrl* c, double now_us, int32_t n_short, cons
                        c->n_short, c->n_long);
         return LAPS_EINVAL;
     }
+    for (int32_t k = 0; k < n_short; ++k)
+        if (std::isnan(q_s[k]) || std::isnan(e_s[k]) || std::isnan(u_s[k])) {
+            laps_set_error("ctrl_step: NaN signal of short instance %d", k);
+            return LAPS_EINVAL;
+        }
+    for (int32_t k = 0; k < n_long; ++k)
+        if (std::isnan(q_l[k]) || std::isnan(e_l[k]) || std::isnan(u_l[k])) {
+            laps_set_error("ctrl_step: NaN signal of long instance %d", k);
+            return LAPS_EINVAL;
+        }
     const double ps = pool_pressure(c, n_short, q_s, e_s, u_s);
     const double pl = pool_pressure(c, n_long, q_l, e_l, u_l);
     *p_short = ps;

@@ -92,6 +92,9 @@ def test_library_ctrl_argument_errors():
     c = api.LapsCtrl(4, 2)
     with pytest.raises(api.LapsError):
         c.laps_ctrl_step(0.0, [(1, 1, 1)], [(1, 1, 1), (2, 2, 2)])       # 1 + 2 signals for pools of 2 + 2
+    with pytest.raises(api.LapsError):
+        c.laps_ctrl_step(0.0, [(1, 1, 1), (1, float("nan"), 1)], [(1, 1, 1), (2, 2, 2)])   # a NaN signal has no rank
+    assert c.n_short == 2
     c.close()
 
 
