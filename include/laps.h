@@ -115,7 +115,7 @@ typedef struct laps_plan_params {
 int laps_plan_buckets(const laps_plan_params* params, int32_t n_req, const int32_t* new_len,
                       const int32_t* prefix_len, laps_plan** out);
 void laps_plan_free(laps_plan* plan);
-/* Accessors return host pointers valid until laps_plan_free. */
+/* Accessors return host pointers valid until laps_plan_free (0 / NULL for a NULL plan). */
 int32_t laps_plan_n_requests(const laps_plan* plan);
 const int32_t* laps_plan_req_class(const laps_plan* plan);   /* [n_req] 0 short, 1 long */
 const int32_t* laps_plan_req_bucket(const laps_plan* plan);  /* [n_req] length-bucket index, -1 if long */

@@ -198,18 +198,18 @@ extern "C" int laps_plan_buckets(const laps_plan_params* p, int32_t n_req, const
 }
 
 extern "C" void laps_plan_free(laps_plan* plan) { delete plan; }
-extern "C" int32_t laps_plan_n_requests(const laps_plan* p) { return (int32_t)p->req_class.size(); }
-extern "C" const int32_t* laps_plan_req_class(const laps_plan* p) { return p->req_class.data(); }
-extern "C" const int32_t* laps_plan_req_bucket(const laps_plan* p) { return p->req_bucket.data(); }
-extern "C" const int32_t* laps_plan_req_batch(const laps_plan* p) { return p->req_batch.data(); }
-extern "C" const int32_t* laps_plan_req_row(const laps_plan* p) { return p->req_row.data(); }
-extern "C" int32_t laps_plan_n_batches(const laps_plan* p) { return (int32_t)p->batch_len_bucket.size(); }
-extern "C" const int32_t* laps_plan_batch_len_bucket(const laps_plan* p) { return p->batch_len_bucket.data(); }
-extern "C" const int32_t* laps_plan_batch_depth(const laps_plan* p) { return p->batch_depth.data(); }
-extern "C" const int32_t* laps_plan_batch_graph_ok(const laps_plan* p) { return p->batch_graph_ok.data(); }
-extern "C" const int32_t* laps_plan_batch_req_offset(const laps_plan* p) { return p->batch_req_offset.data(); }
-extern "C" const int32_t* laps_plan_batch_req_ids(const laps_plan* p) { return p->batch_req_ids.data(); }
-extern "C" int32_t laps_plan_n_long(const laps_plan* p) { return (int32_t)p->long_req.size(); }
-extern "C" const int32_t* laps_plan_long_req(const laps_plan* p) { return p->long_req.data(); }
-extern "C" const int32_t* laps_plan_long_chunk_offset(const laps_plan* p) { return p->long_chunk_offset.data(); }
-extern "C" const int32_t* laps_plan_long_chunk_len(const laps_plan* p) { return p->long_chunk_len.data(); }
+extern "C" int32_t laps_plan_n_requests(const laps_plan* p) { return p ? (int32_t)p->req_class.size() : 0; }
+extern "C" const int32_t* laps_plan_req_class(const laps_plan* p) { return p ? p->req_class.data() : nullptr; }
+extern "C" const int32_t* laps_plan_req_bucket(const laps_plan* p) { return p ? p->req_bucket.data() : nullptr; }
+extern "C" const int32_t* laps_plan_req_batch(const laps_plan* p) { return p ? p->req_batch.data() : nullptr; }
+extern "C" const int32_t* laps_plan_req_row(const laps_plan* p) { return p ? p->req_row.data() : nullptr; }
+extern "C" int32_t laps_plan_n_batches(const laps_plan* p) { return p ? (int32_t)p->batch_len_bucket.size() : 0; }
+extern "C" const int32_t* laps_plan_batch_len_bucket(const laps_plan* p) { return p ? p->batch_len_bucket.data() : nullptr; }
+extern "C" const int32_t* laps_plan_batch_depth(const laps_plan* p) { return p ? p->batch_depth.data() : nullptr; }
+extern "C" const int32_t* laps_plan_batch_graph_ok(const laps_plan* p) { return p ? p->batch_graph_ok.data() : nullptr; }
+extern "C" const int32_t* laps_plan_batch_req_offset(const laps_plan* p) { return p ? p->batch_req_offset.data() : nullptr; }
+extern "C" const int32_t* laps_plan_batch_req_ids(const laps_plan* p) { return p ? p->batch_req_ids.data() : nullptr; }
+extern "C" int32_t laps_plan_n_long(const laps_plan* p) { return p ? (int32_t)p->long_req.size() : 0; }
+extern "C" const int32_t* laps_plan_long_req(const laps_plan* p) { return p ? p->long_req.data() : nullptr; }
+extern "C" const int32_t* laps_plan_long_chunk_offset(const laps_plan* p) { return p ? p->long_chunk_offset.data() : nullptr; }
+extern "C" const int32_t* laps_plan_long_chunk_len(const laps_plan* p) { return p ? p->long_chunk_len.data() : nullptr; }

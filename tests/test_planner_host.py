@@ -111,6 +111,9 @@ def test_null_handles_are_rejected_without_touching_the_gpu():
     assert lib.laps_graph_device_bytes(None) == 0
     lib.laps_graph_destroy(None)
     lib.laps_ctx_destroy(None)
+    assert lib.laps_plan_n_batches(None) == 0 and lib.laps_plan_n_long(None) == 0 and lib.laps_plan_n_requests(None) == 0
+    assert not lib.laps_plan_batch_depth(None) and not lib.laps_plan_long_chunk_len(None)
+    lib.laps_plan_free(None)
 
 
 def test_planner_under_address_and_ub_sanitizers(repo_root, tmp_path):
