@@ -617,7 +617,7 @@ def main():
         ctx8.close()
     if not args.no_cpu:
         log("[bench] leg: oracle on host cores")
-        line["cpu_baseline"] = cpu_baseline(cfg, host_layers[:4], n_sample_req=64)
+        line["cpu_baseline"] = cpu_baseline(cfg, host_layers[:4], n_sample_req=96)
     else:
         line["cpu_baseline"] = None
     print(json.dumps(line), flush=True)
