@@ -40,6 +40,33 @@ def pct(v, q):
     return float(np.percentile(np.asarray(v, dtype=np.float64), q)) if len(v) else None
 
 
+def source_digest():
+    """sha256 over the kernel sources: measured counter figures under profiles/ are stamped with it."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2601_11589_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def load_traffic(kernel_key):
+    """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/traffic.json).
+    None when the kernel sources have changed since the measurement: a stale counter reading is not reported."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if t.get("source_sha256") != source_digest():
+        log("[bench] profiles/traffic.json was measured on other kernel sources: traffic = null")
+        return None
+    return t.get("kernels", {}).get(kernel_key, {}).get("hbm_bytes_per_launch")
+
+
 def gemm_shapes(cfg):
     qd = cfg.n_q_heads * cfg.head_dim
     return {"gemm_qkv": (cfg.qkv_dim, cfg.hidden), "gemm_o": (cfg.hidden, qd),
@@ -214,10 +241,18 @@ def run_short(ctx, layers, cfg, token_budget, steps, warmup, profile_kernels, ta
         res["kernel_launches"] = {k: v[1] for k, v in prof.items()}
         res["gemm"] = {"launches": gcnt, "avg_us": gms / gcnt * 1e3, "bytes_per_launch": gbytes / gcnt,
                        "GBps": gbytes / (gms * 1e-3) / 1e9, "TFLOPs": gflops / (gms * 1e-3) / 1e12}
+        # the gate/up projection alone (the dominant kernel): weights + live A rows + the bf16 activation it writes
+        n_gu, k_gu = gemm_shapes(cfg)["gemm_gateup"]
+        gu_bytes = sum(cfg.n_layers * (n_gu * k_gu * 2 + sb.real_tokens * k_gu * 2 + sb.real_tokens * (n_gu // 2) * 2)
+                       for sb in staged)
+        gu_ms, gu_cnt = prof["gemm_gateup"]
+        res["gemm_gateup"] = {"launches": gu_cnt, "avg_us": gu_ms / gu_cnt * 1e3, "bytes_per_launch": gu_bytes / gu_cnt,
+                              "GBps": gu_bytes / (gu_ms * 1e-3) / 1e9}
         # attention: K and V of every visible position are read once per layer (algorithmic bytes)
         kv_bytes = float(np.sum(b.new_len + b.prefix_len)) * cfg.n_kv_heads * cfg.head_dim * 2 * 2 * cfg.n_layers
         ams, acnt = prof["attn"]
         res["attention"] = {"launches": acnt, "avg_us": ams / max(acnt, 1) * 1e3, "kv_MB_per_launch": kv_bytes / max(acnt, 1) / 1e6,
+                            "us_per_layer_batch": ams * 1e3 / (len(staged) * cfg.n_layers),
                             "kv_GBps": kv_bytes / (ams * 1e-3) / 1e9 if ams > 0 else None}
     sr.close()
     return res
@@ -521,6 +556,10 @@ def main():
     ap.add_argument("--loads", type=str, default="0.7",
                     help="dual queue: Poisson arrival rates as fractions of the unified back-to-back service rate")
     ap.add_argument("--long-steps", type=int, default=2)
+    ap.add_argument("--reprefill-token-max", action="store_true",
+                    help="also run the re-prefill workload with token budget 4096")
+    ap.add_argument("--detail-file", type=str, default="bench_detail.json",
+                    help="file under gpurun_out/ that receives the full record (per-shape tables, samples, trajectories)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "readings of the same run can be scaled to bytes")
@@ -556,31 +595,44 @@ def main():
     short = run_short(ctx, layers, cfg, args.token_budget, args.steps, args.warmup, True, "short",
                       two_streams=not args.no_two_streams)
     g = short.pop("gemm")
-    # HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
-    # plain copy of known size (profiles/short_bucket_gemm_hbm_traffic.md); valid for the default token budget
-    traffic = 270.9e6 if args.token_budget == 128 else None
+    gu = short.pop("gemm_gateup")
+    detail = {"short": short, "short_all_gemms": g}
+    traffic = load_traffic("gemm_gateup_skinny") if args.token_budget == 128 else None
+    weights_bytes = 2.0 * cfg.params_per_layer * cfg.n_layers          # bf16 weights streamed once per replay
+    replay_ms = short["ms_per_step"] / short["n_batches"]
     line = {
         "metric": METRIC, "value": short["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": short["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: 256 new prompts U[8,64], buckets {16,32,64}, 4-layer Qwen2.5-32B-shaped stack, "
-                               f"hipGraph per (bucket, depth), token_budget {args.token_budget} padded tokens per graph",
-                   "layers": cfg.n_layers, "requests": 256, "token_budget": args.token_budget},
-        "latency_ms": {"p50": short["latency_ms_p50"], "p90": short["latency_ms_p90"],
-                       "what": "per request: stage+replay time of the bucket batch that serves it"},
-        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<128,256,2,4,*,2> (gate/up, down) and gemm_kernel<128,128,2,2,0,2> (q/k/v, o): all four projections of every layer",
-                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": g["GBps"] / HBM_PEAK_GBS,
-                     "traffic": traffic, "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"],
-                     "launches": g["launches"], "TFLOPs": g["TFLOPs"]},
-        "short": short,
+        "config": {"workload": "configs[1]: 256 new prompts U[8,64], buckets {16,32,64}, 4-layer Qwen2.5-32B-shaped "
+                               f"stack, hipGraph per (bucket, depth), token_budget {args.token_budget}",
+                   "layers": cfg.n_layers, "requests": 256, "token_budget": args.token_budget,
+                   "batches_per_step": short["n_batches"]},
+        "latency_ms": {"p50": short["latency_ms_p50"], "p90": short["latency_ms_p90"]},
+        # the dominant kernel: the gate/up projection with the fused SwiGLU epilogue on the streaming tile
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<128,256,2,4,2,2> (gate/up + SwiGLU)",
+                     "achieved": gu["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu["GBps"] / HBM_PEAK_GBS,
+                     "traffic": traffic, "avg_launch_us": gu["avg_us"], "bytes_per_launch": gu["bytes_per_launch"],
+                     "launches": gu["launches"]},
+        "roofline_all_gemms": {"achieved": g["GBps"], "unit": "GB/s", "frac": g["GBps"] / HBM_PEAK_GBS,
+                               "avg_launch_us": g["avg_us"], "launches": g["launches"]},
+        # whole replay (all kernels, staging and gaps) against the weights it must stream once
+        "roofline_per_replay": {"bytes": weights_bytes, "ms": replay_ms,
+                                "achieved": weights_bytes / (replay_ms * 1e-3) / 1e9, "unit": "GB/s",
+                                "frac": weights_bytes / (replay_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if "two_streams" in short:
+        line["short_two_streams_tokens_per_s"] = short["two_streams"]["tokens_per_s"]
     if not args.no_token_max:
         log("[bench] leg: short buckets, token-max")
         tm = run_short(ctx, layers, cfg, 4096, max(2, args.steps // 2), 1, True, "token-max")
         gm = tm.pop("gemm")
+        tm.pop("gemm_gateup")
         tm["gemm_TFLOPs"] = gm["TFLOPs"]
         tm["gemm_frac_of_mfma_peak"] = gm["TFLOPs"] / MFMA_BF16_PEAK_TFS
-        line["short_token_max"] = tm
+        detail["short_token_max"] = tm
+        line["short_token_max"] = {"tokens_per_s": tm["tokens_per_s"], "latency_ms_p50": tm["latency_ms_p50"],
+                                   "gemm_frac_of_mfma_peak": tm["gemm_frac_of_mfma_peak"]}
     if not args.no_token_max and args.budget_sweep:
         # the same short workload at token budgets between the latency-oriented default and token-max
         log("[bench] leg: short buckets, token budget sweep")
@@ -588,39 +640,74 @@ def main():
         for tb in (int(x) for x in args.budget_sweep.split(",")):
             r = run_short(ctx, layers, cfg, tb, max(2, args.steps // 2), 1, False, f"budget-{tb}")
             sweep[str(tb)] = {k: r[k] for k in ("tokens_per_s", "ms_per_step", "n_batches", "latency_ms_p50", "latency_ms_p90")}
-        line["short_budget_sweep"] = sweep
+        detail["short_budget_sweep"] = sweep
     if not args.no_reprefill:
         # configs[2]: multi-turn re-prefill, 128 requests of U[16,64] new tokens over U[512,4096] cached tokens
         log("[bench] leg: re-prefill (configs[2])")
         rp = run_short(ctx, layers, cfg, args.token_budget, max(2, args.steps // 2), 1, True, "re-prefill", config=3)
         rp.pop("gemm")
-        line["reprefill"] = rp
+        rp.pop("gemm_gateup")
+        detail["reprefill"] = rp
+        line["reprefill"] = {"tokens_per_s": rp["tokens_per_s"], "latency_ms_p50": rp["latency_ms_p50"],
+                             "latency_ms_p90": rp["latency_ms_p90"], "attn_kv_GBps": rp["attention"]["kv_GBps"],
+                             "attn_us_per_layer": rp["attention"]["us_per_layer_batch"]}
+        if args.reprefill_token_max:
+            log("[bench] leg: re-prefill, token-max")
+            rp2 = run_short(ctx, layers, cfg, 4096, max(2, args.steps // 2), 1, True, "re-prefill-4096", config=3)
+            rp2.pop("gemm")
+            rp2.pop("gemm_gateup")
+            detail["reprefill_token_max"] = rp2
+            line["reprefill_token_max"] = {"tokens_per_s": rp2["tokens_per_s"], "latency_ms_p50": rp2["latency_ms_p50"],
+                                           "attn_kv_GBps": rp2["attention"]["kv_GBps"]}
     if not args.no_long:
         log("[bench] leg: long prefill (configs[3])")
-        line["long_prefill"] = run_long(ctx, layers, cfg, args.long_steps, 1)
+        lp = run_long(ctx, layers, cfg, args.long_steps, 1)
+        detail["long_prefill"] = lp
+        line["long_prefill"] = {"tokens_per_s": lp["tokens_per_s"], "ms_per_step": lp["ms_per_step"],
+                                "latency_ms_p50": lp["latency_ms_p50"], "latency_ms_p90": lp["latency_ms_p90"],
+                                "roofline": {k: lp["roofline"][k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_us")},
+                                "all_gemm_TFLOPs": lp["all_gemm_TFLOPs"], "attention_TFLOPs": lp["attention_TFLOPs"],
+                                "stack_frac_of_mfma_peak": lp["stack_frac_of_mfma_peak"]}
     if not args.no_latency_model:
         log("[bench] leg: latency model fit")
-        line["latency_model"] = run_latency_model(layers, cfg)
+        lm = run_latency_model(layers, cfg)
+        detail["latency_model"] = lm
+        line["latency_model"] = {k: lm[k] for k in ("alpha", "beta", "gamma_w", "gamma_r", "weight_floor_us") if k in lm}
+        line["latency_model"]["knee_tokens_H0"] = lm["knee_with_weight_floor"]["0"]
     if not args.no_graph_cost:
         log("[bench] leg: graph cost table")
-        line["graph_cost"] = run_graph_cost(ctx, layers)
-        if "long_prefill" in line:
-            gc = line["graph_cost"]["models"]["32B"]["replay_ms"]
-            lp = line["long_prefill"]
-            line["pool_sim"] = run_pool_sim({2: gc["64x2"], 64: gc["64x64"]}, lp["ms_per_step"] / lp["n_chunks"])
+        detail["graph_cost"] = run_graph_cost(ctx, layers)
+        if "long_prefill" in detail:
+            gc = detail["graph_cost"]["models"]["32B"]["replay_ms"]
+            lp = detail["long_prefill"]
+            detail["pool_sim"] = run_pool_sim({2: gc["64x2"], 64: gc["64x64"]}, lp["ms_per_step"] / lp["n_chunks"])
     if not args.no_dual_queue:
         cfg8 = inputs.qwen32b_cfg(8)
         log("[bench] leg: dual queue (configs[4])")
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)
-        line["dual_queue"] = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")],
-                                            tuple(float(x) for x in args.loads.split(",")))
+        dq = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")],
+                            tuple(float(x) for x in args.loads.split(",")))
         ctx8.close()
+        detail["dual_queue"] = dq
+        line["dual_queue"] = {"load": dq["poisson"][0].get("load") if dq["poisson"] else None,
+                              "policies": [{"mode": r["mode"], "makespan_ms": round(r["makespan_ms"], 1),
+                                            "short_p50_p90_ms": [round(r["short_latency_ms"][q], 2) for q in ("p50", "p90")],
+                                            "long_p50_p90_ms": [round(r["long_latency_ms"][q], 1) for q in ("p50", "p90")]}
+                                           for r in dq["poisson"]]}
     if not args.no_cpu:
         log("[bench] leg: oracle on host cores")
         line["cpu_baseline"] = cpu_baseline(cfg, host_layers[:4], n_sample_req=96)
     else:
         line["cpu_baseline"] = None
-    print(json.dumps(line), flush=True)
+    # everything bulky (per-shape tables, samples, trajectories) goes to a side file; stdout carries one compact line
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    detail_path = os.path.join(ROOT, "gpurun_out", args.detail_file)
+    with open(detail_path, "w") as f:
+        json.dump({"line": line, "detail": detail}, f)
+    line["detail_file"] = os.path.relpath(detail_path, ROOT)
+    out = json.dumps(line, separators=(",", ":"), default=float)
+    log(f"[bench] result line: {len(out)} bytes; full record in {line['detail_file']}")
+    print(out, flush=True)
 
 
 if __name__ == "__main__":

@@ -247,6 +247,17 @@ void laps_graph_destroy(laps_graph* g);
 size_t laps_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t split_k);
 int laps_gemm_bf16(laps_ctx* ctx, const void* a_dev, const void* w_dev, float* c_dev, int32_t m, int32_t n,
                    int32_t k, int32_t split_k, void* workspace_dev, size_t workspace_bytes, void* stream);
+/* The same projection with the epilogue the layer driver fuses (steps x1 = x + attn W_o^T, y = x1 + act W_d^T and
+ * act = silu(r2 W_g^T) * (r2 W_u^T) of the layer math above), launched as the driver launches it: inside the GEMM
+ * kernel when the plan keeps K in one slice, else K-slice partial sums and the row kernel that adds them.
+ *   epilogue 1: out_f32[m,n] = resid[m,n] + C (resid may alias out_f32; n <= 8192);
+ *   epilogue 2: out_bf16[m,n/2] = silu(gate) * up, with W holding gate and up rows interleaved in blocks of 32 as
+ *               laps_pack_gate_up writes them.
+ * workspace_dev: split * m * n * 4 bytes when laps_gemm_plan_info(m, n, k, 0, epilogue) reports split > 1.
+ * EINVAL on NULL / unsupported shapes or a missing operand, ENOMEM if the workspace is too small. */
+int laps_gemm_epilogue_bf16(laps_ctx* ctx, const void* a_dev, const void* w_dev, int32_t m, int32_t n, int32_t k,
+                            int32_t epilogue, const float* resid_dev, float* out_f32_dev, void* out_bf16_dev,
+                            void* workspace_dev, size_t workspace_bytes, void* stream);
 /* Ragged paged causal GQA attention alone: q_dev bf16 [n_tokens, n_q*hd] (already rotated), K/V of
  * prefix and new tokens already in the pools; out_dev bf16 [n_tokens, n_q*hd]; workspace as for
  * laps_prefill_layer. */

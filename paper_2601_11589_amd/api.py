@@ -103,6 +103,18 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
+def _after_current(stream):
+    """Orders `stream` behind torch's current stream.  What a wrapper allocates (outputs, workspace) and what the
+    caller has just filled (page tables, lengths, inputs) belongs to the current stream; the library enqueues on
+    `stream`, which does not wait for another stream by itself - a page table read before it is written steers the
+    K/V append to wherever the stale entries point.  One event record + wait, nothing when the two are the same."""
+    if stream is None:
+        return
+    cur = torch.cuda.current_stream()
+    if cur.cuda_stream != stream.cuda_stream:
+        stream.wait_stream(cur)
+
+
 def _i32(a):
     a = np.ascontiguousarray(a, dtype=np.int32)
     return a, a.ctypes.data_as(C.POINTER(C.c_int32))
@@ -336,6 +348,7 @@ class LapsCtx:
     # ---- weights
     def laps_pack_gate_up(self, w_gate: torch.Tensor, w_up: torch.Tensor, stream=None) -> torch.Tensor:
         dst = torch.empty((2 * self.cfg.intermediate, self.cfg.hidden), dtype=torch.bfloat16, device=w_gate.device)
+        _after_current(stream)
         _check(lib().laps_pack_gate_up(self._h, _p(w_gate), _p(w_up), _p(dst), _stream(stream)))
         return dst
 
@@ -367,6 +380,7 @@ class LapsCtx:
     def laps_kv_scatter(self, cu, start_pos, page_table, k_src, v_src, k_pool, v_pool, stream=None):
         n_seq, n_tok = cu.numel() - 1, k_src.shape[0]
         self._guard_pools(k_pool)
+        _after_current(stream)
         _check(lib().laps_kv_scatter(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(start_pos), _p(page_table),
                                      C.c_int32(page_table.shape[1]), _p(k_src), _p(v_src), _p(k_pool), _p(v_pool),
                                      _stream(stream)))
@@ -377,6 +391,7 @@ class LapsCtx:
         k = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
         v = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
         self._guard_pools(k_pool)
+        _after_current(stream)
         _check(lib().laps_kv_gather(self._h, C.c_int32(n_seq), C.c_int32(n_tokens), _p(cu), _p(start_pos), _p(page_table),
                                     C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(k), _p(v), _stream(stream)))
         return k, v
@@ -389,6 +404,7 @@ class LapsCtx:
         ws = self.workspace(n_tok, n_seq)
         arr = self._weights_array([w])
         self._guard_pools(k_pool)
+        _after_current(stream)
         _check(lib().laps_prefill_layer(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                         _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(x_in),
                                         _p(x_out), _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
@@ -403,6 +419,7 @@ class LapsCtx:
         kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
         vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
         self._guard_pools(k_pools[0])
+        _after_current(stream)
         _check(lib().laps_prefill_stack(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                         _p(page_table), C.c_int32(page_table.shape[1]), kp, vp, _p(x_in), _p(x_out), _p(ws),
                                         C.c_size_t(ws.numel()), _stream(stream)))
@@ -415,15 +432,37 @@ class LapsCtx:
         out = torch.empty((m, n), dtype=torch.float32, device=a.device)
         need = int(lib().laps_gemm_workspace_bytes(C.c_int32(m), C.c_int32(n), C.c_int32(k), C.c_int32(split_k)))
         ws = torch.empty(max(need, 256), dtype=torch.uint8, device=a.device)
+        _after_current(stream)
         _check(lib().laps_gemm_bf16(self._h, _p(a), _p(w), _p(out), C.c_int32(m), C.c_int32(n), C.c_int32(k),
                                     C.c_int32(split_k), _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
         return out
+
+    def laps_gemm_plan_info(self, m, n, k, split_k=0, epilogue=0) -> dict:
+        out = (C.c_int32 * 7)()
+        _check(lib().laps_gemm_plan_info(C.c_int32(m), C.c_int32(n), C.c_int32(k), C.c_int32(split_k), C.c_int32(epilogue), out))
+        return dict(zip(("bm", "bn", "split", "k_per_split", "epi", "ws", "workgroups"), (int(v) for v in out)))
+
+    def laps_gemm_epilogue_bf16(self, a, w, epilogue: int, resid=None, stream=None):
+        """epilogue 1: returns fp32 resid + a w^T; epilogue 2: returns bf16 silu(gate) * up (w packed by laps_pack_gate_up)."""
+        m, k = a.shape
+        n = w.shape[0]
+        info = self.laps_gemm_plan_info(m, n, k, 0, epilogue)
+        need = info["split"] * m * n * 4 if info["split"] > 1 else 0
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=a.device)
+        out_f32 = torch.empty((m, n), dtype=torch.float32, device=a.device) if epilogue == 1 else None
+        out_bf16 = torch.empty((m, n // 2), dtype=torch.bfloat16, device=a.device) if epilogue == 2 else None
+        _after_current(stream)
+        _check(lib().laps_gemm_epilogue_bf16(self._h, _p(a), _p(w), C.c_int32(m), C.c_int32(n), C.c_int32(k),
+                                             C.c_int32(epilogue), _p(resid), _p(out_f32), _p(out_bf16), _p(ws),
+                                             C.c_size_t(ws.numel()), _stream(stream)))
+        return out_f32 if epilogue == 1 else out_bf16
 
     def laps_attention(self, cu, seq_len, prefix_len, page_table, k_pool, v_pool, q, stream=None):
         n_seq, n_tok = cu.numel() - 1, q.shape[0]
         out = torch.zeros_like(q)
         ws = self.workspace(n_tok, n_seq)
         self._guard_pools(k_pool)
+        _after_current(stream)
         _check(lib().laps_attention(self._h, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                     _p(page_table), C.c_int32(page_table.shape[1]), _p(k_pool), _p(v_pool), _p(q), _p(out),
                                     _p(ws), C.c_size_t(ws.numel()), _stream(stream)))
@@ -455,6 +494,7 @@ class LapsGraph:
         vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
         self._h = C.c_void_p()
         ctx._guard_pools(k_pools[0])
+        _after_current(stream)
         _check(lib().laps_graph_capture(ctx._h, arr, C.c_int32(len_bucket), C.c_int32(depth), C.c_int32(max_pages), kp, vp,
                                         C.c_void_p(stream.cuda_stream), C.byref(self._h)))
 
@@ -462,6 +502,7 @@ class LapsGraph:
         """x_rows: fp32 [sum of the lengths, hidden] on the device, the sequences packed in slot order (or None)."""
         assert page_table is None or page_table.shape[1] == self.max_pages
         n_rows = 0 if x_rows is None else int(x_rows.shape[0])
+        _after_current(stream)       # the staged arrays may have been filled on the current stream
         _check(lib().laps_graph_stage(self._h, C.c_int32(n_real), _p(seq_len), _p(prefix_len), _p(page_table), _p(x_rows),
                                       C.c_int32(n_rows), _stream(stream)))
 
@@ -469,6 +510,7 @@ class LapsGraph:
         _check(lib().laps_graph_replay(self._h, _stream(stream)))
 
     def laps_graph_read_output(self, n_rows: int, dst: torch.Tensor, stream=None):
+        _after_current(stream)       # dst may be a fresh allocation of the current stream
         _check(lib().laps_graph_read_output(self._h, C.c_int32(n_rows), _p(dst), _stream(stream)))
         return dst
 

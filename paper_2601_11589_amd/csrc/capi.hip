@@ -373,11 +373,13 @@ extern "C" int laps_prefill_layer(laps_ctx* c, const laps_layer_weights* w, int3
                       static_cast<hipStream_t>(stream));
 }
 
-extern "C" int laps_prefill_stack(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
-                                  const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
-                                  const int32_t* page_table, int32_t max_pages, void* const* k_pools,
-                                  void* const* v_pools, const float* x_in, float* x_out, void* ws, size_t ws_bytes,
-                                  void* stream) {
+// no_events: never create or record timing events, whatever laps_prof_enable said (the entry point that must
+// not allocate: hipEventCreate and the event list's growth are allocations)
+static int prefill_stack_impl(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                              const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
+                              const int32_t* page_table, int32_t max_pages, void* const* k_pools,
+                              void* const* v_pools, const float* x_in, float* x_out, void* ws, size_t ws_bytes,
+                              void* stream, bool no_events) {
     if (!c) {
         laps_set_error("prefill_stack: NULL context");
         return LAPS_EINVAL;
@@ -394,8 +396,17 @@ extern "C" int laps_prefill_stack(laps_ctx* c, const laps_layer_weights* w, int3
             return LAPS_EINVAL;
         }
     const BatchDesc b{n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages};
-    return run_layers(c, w, c->cfg.n_layers, b, k_pools, v_pools, x_in, x_out, static_cast<unsigned char*>(ws), false,
+    return run_layers(c, w, c->cfg.n_layers, b, k_pools, v_pools, x_in, x_out, static_cast<unsigned char*>(ws), no_events,
                       static_cast<hipStream_t>(stream));
+}
+
+extern "C" int laps_prefill_stack(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                                  const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
+                                  const int32_t* page_table, int32_t max_pages, void* const* k_pools,
+                                  void* const* v_pools, const float* x_in, float* x_out, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    return prefill_stack_impl(c, w, n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages, k_pools, v_pools,
+                              x_in, x_out, ws, ws_bytes, stream, false);
 }
 
 // ----------------------------------------------------------------------------- helpers
@@ -477,6 +488,42 @@ extern "C" int laps_gemm_bf16(laps_ctx* c, const void* a, const void* w, float* 
     }
     const int rows = (int)(((size_t)m * n) / cols);
     return laps_launch_epi_resid(static_cast<const float*>(ws), p.split, nullptr, out, nullptr, nullptr, rows, cols, 1.f, nullptr, s);
+}
+
+// One projection with the epilogue the layer driver asks for, launched exactly as the driver launches it: fused
+// into the GEMM when K is a single slice, else K-slice partial sums followed by the row kernel that adds them.
+extern "C" int laps_gemm_epilogue_bf16(laps_ctx* c, const void* a, const void* w, int32_t m, int32_t n, int32_t k,
+                                       int32_t epilogue, const float* resid, float* out_f32, void* out_bf16, void* ws,
+                                       size_t ws_bytes, void* stream) {
+    if (!c || !a || !w || m < 1 || n < 64 || n % 64 || k < 64 || k % 64) {
+        laps_set_error("gemm_epilogue: NULL pointer or unsupported shape (m=%d n=%d k=%d)", m, n, k);
+        return LAPS_EINVAL;
+    }
+    if ((epilogue == EPI_RESID && (!resid || !out_f32)) || (epilogue == EPI_SWIGLU && (!out_bf16 || n % 64)) ||
+        (epilogue != EPI_RESID && epilogue != EPI_SWIGLU)) {
+        laps_set_error("gemm_epilogue: epilogue %d needs its operands (1: resid, out_f32; 2: out_bf16)", epilogue);
+        return LAPS_EINVAL;
+    }
+    if (epilogue == EPI_RESID && n > 8192) {
+        laps_set_error("gemm_epilogue: the residual row kernel handles rows of at most 8192 columns (n=%d)", n);
+        return LAPS_EINVAL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const GemmPlan p = laps_gemm_plan(m, n, k, 0, epilogue);
+    if (p.epi == epilogue)
+        return laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k, out_f32, resid,
+                                static_cast<bf16_t*>(out_bf16), nullptr, s);
+    const size_t need = (size_t)p.split * m * n * sizeof(float);
+    if (!ws || ws_bytes < need || ((uintptr_t)ws & 255)) {
+        laps_set_error("gemm_epilogue: this shape splits K and needs %zu bytes of 256-byte aligned workspace", need);
+        return LAPS_ENOMEM;
+    }
+    LAPS_TRY(laps_gemm_launch(p, static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(w), m, n, k,
+                              static_cast<float*>(ws), nullptr, nullptr, nullptr, s));
+    if (epilogue == EPI_RESID)
+        return laps_launch_epi_resid(static_cast<const float*>(ws), p.split, resid, out_f32, nullptr, nullptr, m, n, 1.f,
+                                     nullptr, s);
+    return laps_launch_epi_swiglu(static_cast<const float*>(ws), p.split, static_cast<bf16_t*>(out_bf16), m, n / 2, nullptr, s);
 }
 
 extern "C" int laps_attention(laps_ctx* c, int32_t n_seq, int32_t n_tokens, const int32_t* cu, const int32_t* seq_len,

@@ -93,6 +93,7 @@ class DualQueue:
         self.out = torch.zeros_like(d_x) if keep_outputs else None
         ctx.workspace(max(params.unified_budget, params.long_chunk), min(self.n, params.unified_budget))
         self._ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        self.stream.wait_stream(torch.cuda.current_stream())   # self.out and the page table were filled on that stream
 
     # ------------------------------------------------------------------ timed execution of one step
     def _timed(self, fn) -> float:

@@ -10,11 +10,14 @@ points (normed rows, q, k, v, attention output, MLP activation - the MFMA operan
 the fp64 oracle with only those roundings applied already deviates from the pure oracle by ~5.7e-3
 relative L2 per layer (max-abs ~0.13), because each bf16 rounding injects ~1.6e-3 relative noise and
 the MLP branch (std ~4.3) amplifies it.  So here the tests (a) always print the error against the
-pure oracle and say whether the stated bar is met, and (b) require the device error to stay within
-1.3x (relative L2) and 2x (max-abs, an extreme-value statistic) of the deviation that the declared
-storage points alone produce in fp64 arithmetic on the same inputs - i.e. the kernels add nothing
-beyond the bf16 operand format.  The tiny configuration meets the stated bar outright
-(test_gpu_kernels.py).
+pure oracle and say whether the stated bar is met, and (b) hold the device error to the deviation that
+the declared storage points alone produce in fp64 arithmetic on the same inputs, at three grains:
+relative L2 of the sample and of every sequence within 1.1x, the error norm of every row within 1.25x,
+and every single element within 7.5 standard deviations of its row's noise (assert_parity) - i.e. the
+kernels add nothing beyond the bf16 operand format, and one wrong value of a few tenths fails.  The
+stages themselves (every projection at its real tiles, the fused epilogues, attention of a 2048-row
+chunk over 6144 cached keys, the appended K/V) meet fp64 without such a floor in test_gpu_stages_32b.py
+and assert_new_kv.  The tiny configuration meets the stated bar outright (test_gpu_kernels.py).
 """
 import os
 
@@ -32,9 +35,25 @@ LEN_BUCKETS = [16, 32, 64]
 DEPTHS = [1, 2, 4, 8, 16, 32, 64]
 
 
+# Measured on MI355X over all configurations: a row's error norm is 1.00-1.12 x its floor (median 1.005), a
+# sequence's 1.00-1.01 x, and the largest single deviation is 5.3-6.2 standard deviations of its row's noise (the
+# extreme of ~2e7 Gaussian-like values).  The factors below leave a small margin over that.
+ROW_FACTOR = 1.25    # a row's error norm may exceed the noise floor of that row by this factor
+SEQ_FACTOR = 1.1     # a sequence's (and the whole sample's) relative L2 error, likewise
+ELEM_SIGMAS = 7.5    # no element may be off by more than this many standard deviations of its row's noise
+
+
 def assert_parity(tag, got, case, seqs, oracle_cache=None):
     """Returns (rel, max_abs, rel_floor): device-vs-pure errors and the storage-point noise floor.
-    oracle_cache: dict reused when several device runs are checked against the same oracle outputs."""
+    oracle_cache: dict reused when several device runs are checked against the same oracle outputs.
+
+    Checked against the pure fp64 oracle y, with the deviation of the fp64 oracle that applies the declared bf16
+    storage points (ys) as the noise floor of the operand format:
+      * the whole sample and every sequence: relative L2 <= max(stated bar, SEQ_FACTOR x floor of that sequence);
+      * every row: error norm <= ROW_FACTOR x the floor's error norm of that row (or the stated bar);
+      * every element: |error| <= ELEM_SIGMAS x the per-element noise of its row (floor error norm / sqrt(d)), or the
+        stated max-abs bar - so a single wrong value of a few tenths fails, where a pooled max-abs bound of twice
+        the floor's extreme value would let it pass."""
     if oracle_cache is not None and "y" in oracle_cache:
         y, ys = oracle_cache["y"], oracle_cache["ys"]
     else:
@@ -42,16 +61,51 @@ def assert_parity(tag, got, case, seqs, oracle_cache=None):
         ys, _, _, _ = case.oracle(storage_rounding=True, seqs=seqs)
         if oracle_cache is not None:
             oracle_cache["y"], oracle_cache["ys"] = y, ys
+    got = np.asarray(got, np.float64)
     rel, mx = errors(got, y)
     rel_f, mx_f = errors(ys, y)
     strict = rel < REL_L2_TOL and mx < MAX_ABS_TOL
+    assert np.all(np.isfinite(got))
+    d = y.shape[1]
+    err_row = np.linalg.norm(got - y, axis=1)
+    flo_row = np.linalg.norm(ys - y, axis=1)
+    ref_row = np.linalg.norm(y, axis=1)
+    row_ratio = err_row / np.maximum(flo_row, 1e-300)
+    sigma = np.maximum(flo_row, err_row * 0) / np.sqrt(d)
+    z = np.abs(got - y) / np.maximum(sigma[:, None], 1e-300)
     print(f"[parity] {tag}: device vs fp64 oracle rel_l2={rel:.3e} max_abs={mx:.3e} | bf16 storage points alone "
           f"(fp64 arithmetic) rel_l2={rel_f:.3e} max_abs={mx_f:.3e} | stated bar (5e-3, 2e-2) "
-          f"{'MET' if strict else 'NOT met (bf16 operand noise)'}", flush=True)
-    assert np.all(np.isfinite(got))
-    assert rel < max(REL_L2_TOL, 1.3 * rel_f), (tag, rel, rel_f)
-    assert mx < max(MAX_ABS_TOL, 2.0 * mx_f), (tag, mx, mx_f)
+          f"{'MET' if strict else 'NOT met (bf16 operand noise)'} | per row: error / floor max {row_ratio.max():.3f} "
+          f"median {np.median(row_ratio):.3f}; per element: max {z.max():.2f} sigma of its row's noise", flush=True)
+    assert rel < max(REL_L2_TOL, SEQ_FACTOR * rel_f), (tag, rel, rel_f)
+    ids = list(range(case.n)) if seqs is None else list(seqs)
+    o = 0
+    for i in ids:
+        n = int(case.new_len[i])
+        r_s, _ = errors(got[o:o + n], y[o:o + n])
+        f_s, _ = errors(ys[o:o + n], y[o:o + n])
+        assert r_s < max(REL_L2_TOL, SEQ_FACTOR * f_s), (tag, "sequence", i, r_s, f_s)
+        o += n
+    assert o == got.shape[0]
+    bad_rows = err_row > np.maximum(ROW_FACTOR * flo_row, REL_L2_TOL * ref_row)
+    assert not bad_rows.any(), (tag, "rows", np.nonzero(bad_rows)[0][:8], row_ratio[bad_rows][:8])
+    bad = np.abs(got - y) > np.maximum(ELEM_SIGMAS * sigma[:, None], MAX_ABS_TOL)
+    assert not bad.any(), (tag, "elements", int(bad.sum()), float(z.max()))
     return rel, mx, rel_f
+
+
+def assert_new_kv(tag, case, layer, seqs, ks, vs):
+    """Appended K and V of `layer` for the sampled sequences against the oracle's: at layer 0 two roundings (the normed
+    row, the stored value) separate them, deeper layers inherit the noise of the residual stream."""
+    k_gpu, v_gpu = case.gathered_new_kv(layer)
+    for what, g, want in (("k", k_gpu, ks), ("v", v_gpu, vs)):
+        got = np.concatenate([g[case.cu[i]:case.cu[i + 1]] for i in seqs])
+        rel, mx = errors(got, np.concatenate(want))
+        print(f"[parity] {tag}: appended {what} of layer {layer}: rel_l2={rel:.3e} max_abs={mx:.3e}", flush=True)
+        assert rel < 4e-3, (tag, what, rel)
+        # element by element: one bf16 half-ulp of the stored value plus the propagated rounding of the normed row
+        w = np.concatenate(want)
+        assert np.all(np.abs(got - w) <= np.abs(w) * 2.0 ** -8 + 0.03), (tag, what, float(np.max(np.abs(got - w))))
 
 
 @pytest.fixture(scope="module")
@@ -138,14 +192,19 @@ def test_config2_short_buckets_as_graphs(model):
     assert sorted(ys) == list(range(256))
     assert all(np.all(np.isfinite(v)) for v in ys.values())
     order = np.argsort(b.new_len)
-    sample = sorted({int(order[0]), int(order[-1]), int(order[128]), 0, 255, 100})
+    # 36 of the 256 requests: the shortest and longest, every 8th in arrival order, and the first and last
+    sample = sorted({int(order[0]), int(order[-1]), int(order[128]), 0, 255, 100} | set(range(3, 256, 8)))
+    assert len(sample) >= 32
     got = np.concatenate([ys[i] for i in sample])
-    _, _, floor = assert_parity("config2 (6 sampled requests, graphs, budget 128)", got, case, sample)
+    cache = {}
+    _, _, floor = assert_parity(f"config2 ({len(sample)} sampled requests, graphs, budget 128)", got, case, sample, cache)
+    _, ks, vs, _ = case.oracle(seqs=sample[:8])
+    assert_new_kv("config2", case, 0, sample[:8], ks[0], vs[0])
     # token-max variant (large depths): same requests, same answers up to split-order effects
     case2 = SharedCase(cfg, b.new_len, b.prefix_len, inputs.SEED_BASE + 2, host_layers, dev_layers).to_device(ctx)
     ys2, _ = run_planned_short(case2, cfg, ctx, 4096)
     got2 = np.concatenate([ys2[i] for i in sample])
-    assert_parity("config2 (6 sampled requests, graphs, budget 4096)", got2, case2, sample)
+    assert_parity(f"config2 ({len(sample)} sampled requests, graphs, budget 4096)", got2, case2, sample, cache)
     rel, mx = errors(got2, got)      # two valid bf16 evaluations differ by about sqrt(2) x the noise floor
     print(f"[parity] config2 budget 4096 vs budget 128 on device: rel_l2={rel:.3e} max_abs={mx:.3e}", flush=True)
     assert rel < 2.0 * floor, (rel, floor)
@@ -163,14 +222,15 @@ def test_config3_reprefill_over_paged_prefix(model):
     case = SharedCase(cfg, b.new_len[keep], b.prefix_len[keep], inputs.SEED_BASE + 3, host_layers, dev_layers).to_device(ctx)
     # (a) one packed varlen batch, un-captured
     y = case.run_stack()
-    sample = [0, len(keep) // 2, len(keep) - 1]
-    rows = np.concatenate([np.arange(case.cu[i], case.cu[i + 1]) for i in sample])
-    assert_parity("config3 varlen batch (3 sampled requests)", y[rows], case, sample)
+    cache = {}
+    assert_parity(f"config3 varlen batch (all {len(keep)} kept requests)", y, case, None, cache)
+    _, ks, vs, _ = case.oracle(seqs=[0, len(keep) - 1])
+    assert_new_kv("config3", case, 0, [0, len(keep) - 1], ks[0], vs[0])
     # (b) the same requests through captured bucket graphs
     case_g = SharedCase(cfg, b.new_len[keep], b.prefix_len[keep], inputs.SEED_BASE + 3, host_layers, dev_layers).to_device(ctx)
     ys, _ = run_planned_short(case_g, cfg, ctx, 128)
-    got = np.concatenate([ys[i] for i in sample])
-    assert_parity("config3 bucket graphs (3 sampled requests)", got, case_g, sample)
+    got = np.concatenate([ys[i] for i in range(len(keep))])
+    assert_parity(f"config3 bucket graphs (all {len(keep)} kept requests)", got, case_g, None, cache)
 
 
 def test_prefix_cache_equivalence_at_full_shape(model):
@@ -195,8 +255,10 @@ def test_prefix_cache_equivalence_at_full_shape(model):
 
 
 def test_config4_long_prefill_in_chunks(model):
-    """8 prompts U[1024,8192] in 2048-token chunks; the oracle (unchunked) checks the shortest prompt,
-    the others are checked for finiteness and against an unchunked device pass of a mid-size prompt."""
+    """8 prompts U[1024,8192] in 2048-token chunks; the oracle (unchunked) checks the shortest prompt (one chunk)
+    and the 3251-token one (two chunks: 1203 rows attending to 2048 cached keys that the first chunk appended),
+    the others are checked for finiteness and against an unchunked device pass of a mid-size prompt.  Attention
+    over longer cached ranges (2048 rows over 6144 keys) meets the oracle in test_gpu_stages_32b.py."""
     cfg, ctx, host_layers, dev_layers = model
     b = inputs.make_batch(4)
     case = SharedCase(cfg, b.new_len, b.prefix_len, inputs.SEED_BASE + 4, host_layers, dev_layers).to_device(ctx)
@@ -217,8 +279,11 @@ def test_config4_long_prefill_in_chunks(model):
     i0 = int(np.argmin(case.new_len))
     _, _, floor = assert_parity(f"config4 shortest prompt ({case.new_len[i0]} tokens, chunked)",
                                 y[case.cu[i0]:case.cu[i0 + 1]], case, [i0])
-    # chunked == unchunked on the device for the second shortest prompt
     i1 = int(np.argsort(case.new_len)[1])
+    assert case.new_len[i1] > 2048
+    assert_parity(f"config4 second shortest prompt ({case.new_len[i1]} tokens in 2 chunks) vs the unchunked oracle",
+                  y[case.cu[i1]:case.cu[i1 + 1]], case, [i1])
+    # chunked == unchunked on the device for the same prompt
     solo = SharedCase(cfg, [case.new_len[i1]], [0], inputs.SEED_BASE + 4, host_layers, dev_layers)
     solo.x = case.x[case.cu[i1]:case.cu[i1 + 1]]
     solo.to_device(ctx)
