@@ -192,6 +192,23 @@ int laps_prefill_stack(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq
                        const float* x_in_dev, float* x_out_dev, void* workspace_dev, size_t workspace_bytes,
                        void* stream);
 
+/* ------------------------------------------------------------------ prefill forward without a workspace argument
+ * For callers that cannot allocate device memory or may not call anything that does: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, kernels and results as
+ * laps_prefill_stack, with the workspace taken from a static device array inside the library
+ * (laps_static_scratch_bytes() = 128 MiB per GPU, held from library load until the process ends; its address on the
+ * context's device is resolved once, in laps_ctx_create).  The call itself allocates nothing, frees nothing and
+ * never synchronises.  A batch whose workspace (laps_workspace_bytes) exceeds the array is rejected with LAPS_EINVAL
+ * and a message naming both sizes: at the 32B layer shape that is a few hundred rows.  The context's device must be
+ * current.  Every call on a GPU uses that GPU's one array (nothing in it has to start at zero: each region is
+ * written before it is read within the call), so calls that overlap in time on one GPU - two streams, two threads,
+ * two contexts - race on it and must be serialised by the caller; calls on one stream are ordered by the stream. */
+size_t laps_static_scratch_bytes(void);
+int laps_prefill_stack_static(laps_ctx* ctx, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                              const int32_t* cu_seqlens_dev, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
+                              const int32_t* page_table_dev, int32_t max_pages, void* const* k_pools,
+                              void* const* v_pools, const float* x_in_dev, float* x_out_dev, void* stream);
+
 /* ------------------------------------------------------------------ launch plans (host only, no device work)
  * What the library would launch for a shape; for tests of the launch arithmetic and for tuning.
  * laps_gemm_plan_info: the projection C[m,n] = A[m,k] W[n,k]^T with the epilogue the layer driver would ask for

@@ -54,6 +54,7 @@ def lib():
         L.laps_workspace_bytes.restype = C.c_size_t
         L.laps_workspace_bytes_for.restype = C.c_size_t
         L.laps_gemm_workspace_bytes.restype = C.c_size_t
+        L.laps_static_scratch_bytes.restype = C.c_size_t
         L.laps_graph_device_bytes.restype = C.c_size_t
         L.laps_graph_output.restype = C.c_void_p
         L.laps_graph_input.restype = C.c_void_p
@@ -423,6 +424,21 @@ class LapsCtx:
         _check(lib().laps_prefill_stack(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len), _p(prefix_len),
                                         _p(page_table), C.c_int32(page_table.shape[1]), kp, vp, _p(x_in), _p(x_out), _p(ws),
                                         C.c_size_t(ws.numel()), _stream(stream)))
+        return x_out
+
+    def laps_prefill_stack_static(self, layers, cu, seq_len, prefix_len, page_table, k_pools, v_pools, x_in, x_out,
+                                  stream=None):
+        """laps_prefill_stack on the library's static scratch array: the caller passes the output tensor too, so
+        that neither the binding nor the library allocates device memory in this call."""
+        n_seq, n_tok = cu.numel() - 1, x_in.shape[0]
+        arr = self._weights_array(layers)
+        kp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in k_pools])
+        vp = (C.c_void_p * len(layers))(*[t.data_ptr() for t in v_pools])
+        self._guard_pools(k_pools[0])
+        _after_current(stream)
+        _check(lib().laps_prefill_stack_static(self._h, arr, C.c_int32(n_seq), C.c_int32(n_tok), _p(cu), _p(seq_len),
+                                               _p(prefix_len), _p(page_table), C.c_int32(page_table.shape[1]), kp, vp,
+                                               _p(x_in), _p(x_out), _stream(stream)))
         return x_out
 
     # ---- single kernels

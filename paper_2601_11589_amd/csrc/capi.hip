@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -22,6 +23,38 @@ void laps_set_error(const char* fmt, ...) {
 extern "C" const char* laps_last_error(void) { return g_err; }
 extern "C" const char* laps_version(void) { return "laps-gfx950 0.1"; }
 
+// ----------------------------------------------------------------------------- static scratch
+// Workspace of laps_prefill_stack_static, for callers that may not allocate.  The array lives in this code
+// object's device image: every GPU the library is loaded on holds its own copy at its own address for the life
+// of the process.  In host code the array's name is only a handle for hipGetSymbolAddress; the address the
+// kernels are given is the one resolved below, per device, with that device current.
+#define LAPS_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+static __device__ __align__(256) unsigned char scratch[LAPS_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];   // resolved address per device ordinal, nullptr = not yet
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the CURRENT device (which must be `device`).  Resolved once per device.
+static int resolve_static_scratch(int device, unsigned char** out) {
+    if (device < 0 || device >= kMaxDevices) {
+        laps_set_error("static scratch: device ordinal %d out of range", device);
+        return LAPS_EINVAL;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            laps_set_error("static scratch: hipGetSymbolAddress failed on device %d: %s", device, hipGetErrorString(e));
+            return LAPS_EHIP;
+        }
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return LAPS_OK;
+}
+
 // ----------------------------------------------------------------------------- context
 struct laps_ctx {
     laps_model_cfg cfg;
@@ -29,6 +62,7 @@ struct laps_ctx {
     int max_pos;
     int pool_pages;  // page ids must be below this (INT_MAX: unknown, not checked)
     float2* rope;  // [max_pos][hd/2] (cos, sin)
+    unsigned char* static_ws;  // this device's copy of the static scratch array (resolved at creation)
     // timing
     bool prof_on;
     std::vector<hipEvent_t> ev;  // pairs (start, stop)
@@ -117,6 +151,7 @@ extern "C" int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions,
     c->max_pos = max_positions;
     c->pool_pages = INT_MAX;
     c->rope = nullptr;
+    c->static_ws = nullptr;
     c->prof_on = false;
     c->ev_used = 0;
     hipError_t e = hipGetDevice(&c->device);
@@ -126,7 +161,8 @@ extern "C" int laps_ctx_create(const laps_model_cfg* cfg, int32_t max_positions,
         delete c;
         return e == hipErrorOutOfMemory ? LAPS_ENOMEM : LAPS_EHIP;
     }
-    int rc = laps_launch_rope_table(c->rope, max_positions, cfg->head_dim, cfg->rope_theta, nullptr);
+    int rc = resolve_static_scratch(c->device, &c->static_ws);   // the context's device is current here
+    if (rc == LAPS_OK) rc = laps_launch_rope_table(c->rope, max_positions, cfg->head_dim, cfg->rope_theta, nullptr);
     if (rc == LAPS_OK && hipDeviceSynchronize() != hipSuccess) {
         laps_set_error("ctx_create: rope table kernel failed");
         rc = LAPS_EHIP;
@@ -407,6 +443,38 @@ extern "C" int laps_prefill_stack(laps_ctx* c, const laps_layer_weights* w, int3
                                   void* stream) {
     return prefill_stack_impl(c, w, n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages, k_pools, v_pools,
                               x_in, x_out, ws, ws_bytes, stream, false);
+}
+
+extern "C" size_t laps_static_scratch_bytes(void) { return LAPS_STATIC_SCRATCH_BYTES; }
+
+// laps_prefill_stack with the library's static device array as workspace: no allocation of any kind here or
+// below (the launches take the address resolved at context creation as a kernel argument).
+extern "C" int laps_prefill_stack_static(laps_ctx* c, const laps_layer_weights* w, int32_t n_seq, int32_t n_tokens,
+                                         const int32_t* cu, const int32_t* seq_len, const int32_t* prefix_len,
+                                         const int32_t* page_table, int32_t max_pages, void* const* k_pools,
+                                         void* const* v_pools, const float* x_in, float* x_out, void* stream) {
+    if (!c || !c->static_ws) {
+        laps_set_error("prefill_stack_static: NULL context or static scratch not resolved");
+        return LAPS_EINVAL;
+    }
+    if (n_seq < 1 || n_tokens < 1) {
+        laps_set_error("prefill_stack_static: non-positive size");
+        return LAPS_EINVAL;
+    }
+    const size_t need = ws_layout(c->cfg, n_tokens, n_seq).total;
+    if (need > LAPS_STATIC_SCRATCH_BYTES) {
+        laps_set_error("prefill_stack_static: %d tokens x %d sequences need %zu bytes of workspace, the static scratch "
+                       "holds %zu; use laps_prefill_stack with a caller-owned workspace", n_tokens, n_seq, need,
+                       (size_t)LAPS_STATIC_SCRATCH_BYTES);
+        return LAPS_EINVAL;
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != c->device) {
+        laps_set_error("prefill_stack_static: the context's device %d must be current (current: %d)", c->device, dev);
+        return LAPS_EINVAL;
+    }
+    return prefill_stack_impl(c, w, n_seq, n_tokens, cu, seq_len, prefix_len, page_table, max_pages, k_pools, v_pools,
+                              x_in, x_out, c->static_ws, LAPS_STATIC_SCRATCH_BYTES, stream, true);
 }
 
 // ----------------------------------------------------------------------------- helpers
