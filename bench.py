@@ -441,7 +441,7 @@ def run_pool_sim(short_step_ms_4l, long_chunk_ms_4l, layers_full=64):
 
 
 # ------------------------------------------------------------------------------------- mixed dual-queue step loop
-def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,)):
+def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,), params=None):
     """configs[4]: 4 long + 512 short / re-prefill requests on an 8-layer stack, Poisson arrivals replayed on a
     virtual clock that advances by measured GPU step time.  Unified FCFS mixed batches vs temporal disaggregation."""
     import numpy as np
@@ -457,7 +457,7 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,)):
         p.copy_(torch.randn(p.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
     is_long = b.new_len > 64
     dq = dualqueue.DualQueue(ctx8, layers8, b.new_len, b.prefix_len, b.page_table, d_x, k_pools, v_pools,
-                             dualqueue.DQParams())
+                             params or dualqueue.DQParams())
     zeros = np.zeros(b.n)
     log("[bench:dual-queue] warm-up and back-to-back passes")
     dq.run_disaggregated(zeros, 0.0)          # warm-up: captures every bucket shape the workload needs
@@ -673,7 +673,9 @@ def main():
         lm = run_latency_model(layers, cfg)
         detail["latency_model"] = lm
         line["latency_model"] = {k: lm[k] for k in ("alpha", "beta", "gamma_w", "gamma_r", "weight_floor_us") if k in lm}
-        line["latency_model"]["knee_tokens_H0"] = lm["knee_with_weight_floor"]["0"]
+        line["latency_model"]["knee_tokens_H0"] = lm["knee_library"]["0"]
+        line["latency_model"]["derived"] = {k: lm["derived"][k] for k in ("short_max_len", "short_token_budget", "fuse_budget")}
+        log(f"[bench] schedule parameters from the fit: {line['latency_model']['derived']}")
     if not args.no_graph_cost:
         log("[bench] leg: graph cost table")
         detail["graph_cost"] = run_graph_cost(ctx, layers)
@@ -685,8 +687,16 @@ def main():
         cfg8 = inputs.qwen32b_cfg(8)
         log("[bench] leg: dual queue (configs[4])")
         ctx8 = api.LapsCtx(cfg8, max_positions=8192 + 64)
+        dq_params = None
+        if "latency_model" in detail:
+            # Section 2.1 "runtime fitting": classification boundary and fusion budget come from this run's fit
+            from paper_2601_11589_amd import dualqueue
+            lm = detail["latency_model"]
+            dq_params = dualqueue.DQParams.from_fit((lm["alpha"], lm["beta"], lm["gamma_w"], lm["gamma_r"]),
+                                                    lm["weight_floor_us"], 4096.0, tuple(LEN_BUCKETS), tuple(DEPTHS))
+            log(f"[bench] dual queue runs with short_max_len {dq_params.short_max_len}, fuse budget {dq_params.fuse_budget}")
         dq = run_dual_queue(ctx8, layers_all, cfg8, [float(w) for w in args.windows_us.split(",")],
-                            tuple(float(x) for x in args.loads.split(",")))
+                            tuple(float(x) for x in args.loads.split(",")), dq_params)
         ctx8.close()
         detail["dual_queue"] = dq
         line["dual_queue"] = {"load": dq["poisson"][0].get("load") if dq["poisson"] else None,

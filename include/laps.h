@@ -300,6 +300,26 @@ int laps_prof_read(laps_ctx* ctx, double* ms_out /*[LAPS_K_COUNT]*/, int64_t* co
  * Both return NaN when alpha <= 0 (or H < 0). */
 double laps_lm_boundary_prefill(double alpha, double beta, double gamma_w);
 double laps_lm_boundary_reprefill(double alpha, double beta, double gamma_w, double gamma_r, double hist_len);
+/* Section 2.1 with a constant memory term: a short batch on this hardware is bounded by streaming the layer weights
+ * once per pass (floor_t, same time unit as the coefficients), which the printed T_mem does not contain.  The knee is
+ * the positive root of alpha L^2 + (2 alpha H + beta - gamma_w) L - (floor_t + gamma_r H) = 0: up to that many (padded)
+ * new tokens a step costs one pass over the weights, beyond it arithmetic.  floor_t = 0 gives
+ * laps_lm_boundary_reprefill.  NaN when alpha <= 0, H < 0, floor_t < 0 or an argument is NaN. */
+double laps_lm_knee(double alpha, double beta, double gamma_w, double gamma_r, double floor_t, double hist_len);
+/* "Runtime fitting" closed into the schedule: the parameters that the classification (Section 3.2), the bucket
+ * grid (Section 3.1) and Algorithm 1's batch admission take from a fit coef[4] = {alpha, beta, gamma_w, gamma_r}
+ * and a measured weight-streaming floor.  knee = min(knee(H = 0), knee(H = hist_max)).
+ *   short_max_len      = the largest length bucket <= knee (the smallest bucket if none is);
+ *   short_token_budget = the largest captured shape len_bucket * depth <= knee over buckets <= short_max_len
+ *                        (at least short_max_len * depths[0]): padded tokens per graph in latency mode;
+ *   fuse_budget        = the same value: other length buckets may join a batch up to that many padded tokens.
+ * EINVAL on NULL, an unsorted grid, hist_max < 0 or a fit without a knee. */
+typedef struct laps_lm_params {
+    int32_t short_max_len, short_token_budget, fuse_budget;
+    double knee_fresh, knee_hist; /* knee at H = 0 and at H = hist_max */
+} laps_lm_params;
+int laps_lm_derive_params(const double* coef, double floor_t, double hist_max, int32_t n_len_buckets,
+                          const int32_t* len_buckets, int32_t n_depths, const int32_t* depths, laps_lm_params* out);
 /* Least-squares fit of (alpha, beta) to t_comp and (gamma_w, gamma_r) to t_mem from n samples (host arrays
  * [n]; any consistent time unit).  coef_out[4] = {alpha, beta, gamma_w, gamma_r}.  Either time array may be NULL:
  * that half is not fitted and its two outputs are left untouched.  EINVAL if n < 2, both are NULL, or the
@@ -359,6 +379,28 @@ int laps_awd_begin_round(laps_awd* awd, double free_at_us);
 int laps_awd_poll(laps_awd* awd, double now_us, double rate_hat, int32_t n_waiting, const double* arrival_us,
                   const double* ddl_us, const int32_t* new_len, int32_t* action, int32_t* n_take, int32_t* take_idx,
                   int32_t* len_bucket, int32_t* depth, int32_t* reason, double* wake_us);
+
+/* ------------------------------------------------------------------ fixed-window dispatch of the short queue (host)
+ * Section 3.2 (one class of prefill at a time; two queues) and Section 3.1 (waiting window; graph fusion), read for one
+ * GPU that alternates between the queues.  At a decision instant, over the waiting short requests (host arrays
+ * [n_waiting], arrival order, all arrived by now_us; need_i = the smallest length bucket >= new_len[i]):
+ *   *action = LAPS_AWD_DISPATCH iff a request waits and (now - arrival[0] >= window_us, or the sum of need_i >=
+ *   token_budget, or nothing_else != 0: no long request waits and no arrival is outstanding); all waiting requests then
+ *   leave together, and *fused_len_bucket is the largest need_i if the sum of need_i is below merge_below (every
+ *   request then runs in that one length bucket: one replay costs one pass over the weights whatever its shape), else
+ *   0 (plan each bucket on its own).  Otherwise LAPS_AWD_WAIT with *wake_us = arrival[0] + window_us (INFINITY when
+ *   nothing waits): run a long chunk meanwhile.  *padded_tokens = the sum of need_i.
+ * EINVAL on NULL, an unsorted grid, a length outside the grid, unordered arrivals or one after now_us. */
+typedef struct laps_window_params {
+    int32_t n_len_buckets;
+    const int32_t* len_buckets; /* host, strictly ascending */
+    double window_us;           /* W >= 0 */
+    int64_t token_budget;       /* padded tokens that make the queue leave at once, >= 1 */
+    int64_t merge_below;        /* fuse all waiting requests into one length bucket below this many padded tokens */
+} laps_window_params;
+int laps_window_poll(const laps_window_params* p, double now_us, int32_t n_waiting, const double* arrival_us,
+                     const int32_t* new_len, int32_t nothing_else, int32_t* action, int32_t* fused_len_bucket,
+                     int64_t* padded_tokens, double* wake_us);
 
 /* ------------------------------------------------------------------ instance-pressure controller (host)
  * Algorithm 2 (spatial disaggregation): n_total instances in a SHORT and a LONG pool.  Each control period the

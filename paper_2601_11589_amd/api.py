@@ -69,6 +69,8 @@ def lib():
         L.laps_lm_boundary_prefill.argtypes = [C.c_double] * 3
         L.laps_lm_boundary_reprefill.restype = C.c_double
         L.laps_lm_boundary_reprefill.argtypes = [C.c_double] * 5
+        L.laps_lm_knee.restype = C.c_double
+        L.laps_lm_knee.argtypes = [C.c_double] * 6
         L.laps_awd_window_us.restype = C.c_double
         L.laps_awd_window_us.argtypes = [C.c_void_p]
         L.laps_awd_target_depth.restype = C.c_int32
@@ -163,6 +165,26 @@ def laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len) -> float
     return float(lib().laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r, hist_len))
 
 
+def laps_lm_knee(alpha, beta, gamma_w, gamma_r, floor_t, hist_len) -> float:
+    return float(lib().laps_lm_knee(alpha, beta, gamma_w, gamma_r, floor_t, hist_len))
+
+
+class _LmParams(C.Structure):
+    _fields_ = [("short_max_len", C.c_int32), ("short_token_budget", C.c_int32), ("fuse_budget", C.c_int32),
+                ("knee_fresh", C.c_double), ("knee_hist", C.c_double)]
+
+
+def laps_lm_derive_params(coef, floor_t, hist_max, len_buckets, depths) -> dict:
+    """coef = (alpha, beta, gamma_w, gamma_r).  Returns the scheduling parameters that follow from the fit."""
+    c = (C.c_double * 4)(*[float(v) for v in coef])
+    (lb, lb_p), (dp, dp_p) = _i32(len_buckets), _i32(depths)
+    out = _LmParams()
+    _check(lib().laps_lm_derive_params(c, C.c_double(floor_t), C.c_double(hist_max), C.c_int32(len(lb)), lb_p,
+                                       C.c_int32(len(dp)), dp_p, C.byref(out)))
+    return {"short_max_len": out.short_max_len, "short_token_budget": out.short_token_budget,
+            "fuse_budget": out.fuse_budget, "knee_fresh": out.knee_fresh, "knee_hist": out.knee_hist}
+
+
 def laps_lm_fit(new_len, hist_len, t_comp=None, t_mem=None):
     """Returns (alpha, beta, gamma_w, gamma_r); the pair whose time array is None comes back as NaN."""
     arrs = [None if a is None else np.ascontiguousarray(a, dtype=np.float64) for a in (new_len, hist_len, t_comp, t_mem)]
@@ -247,6 +269,27 @@ class LapsAwd:
             self.close()
         except Exception:
             pass
+
+
+# --------------------------------------------------------------------------- fixed-window dispatch
+class _WindowParams(C.Structure):
+    _fields_ = [("n_len_buckets", C.c_int32), ("len_buckets", C.POINTER(C.c_int32)), ("window_us", C.c_double),
+                ("token_budget", C.c_int64), ("merge_below", C.c_int64)]
+
+
+def laps_window_poll(len_buckets, window_us, token_budget, merge_below, now_us, arrival_us, new_len, nothing_else) -> dict:
+    lb, lb_p = _i32(len_buckets)
+    arr = np.ascontiguousarray(arrival_us, dtype=np.float64)
+    nl, nl_p = _i32(new_len)
+    assert len(arr) == len(nl)
+    prm = _WindowParams(len(lb), lb_p, float(window_us), int(token_budget), int(merge_below))
+    action, fused = C.c_int32(), C.c_int32()
+    padded, wake = C.c_int64(), C.c_double()
+    _check(lib().laps_window_poll(C.byref(prm), C.c_double(now_us), C.c_int32(len(arr)),
+                                  arr.ctypes.data_as(C.POINTER(C.c_double)), nl_p, C.c_int32(int(bool(nothing_else))),
+                                  C.byref(action), C.byref(fused), C.byref(padded), C.byref(wake)))
+    return {"dispatch": action.value == 1, "fused_len_bucket": fused.value, "padded_tokens": padded.value,
+            "wake_us": wake.value}
 
 
 # --------------------------------------------------------------------------- instance-pressure controller

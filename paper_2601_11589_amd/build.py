@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblaps.so")
-SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "capi.hip", "planner.cpp", "latency_model.cpp", "awd.cpp", "pool_ctrl.cpp"]
+SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "capi.hip", "planner.cpp", "latency_model.cpp", "awd.cpp", "pool_ctrl.cpp", "window.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for all device code
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -81,6 +81,48 @@ struct GemmArgs {
                            // every tile shape skips a row tile that holds nothing else (its output is then not written)
 };
 
+// Writes a workgroup's accumulators with the requested epilogue.  Accumulator layout of the 32x32 MFMA:
+// lane -> column (lane & 31); register r -> row 8*(r/4) + 4*(lane/32) + r%4.
+template <typename T, int EPI>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[T::MI][T::NI], const GemmArgs& g, int ks, int m0, int n0,
+                                           int wm, int wn, int lrow, int lk) {
+    const int M = g.M, N = g.N;
+    if constexpr (EPI == EPI_PARTIAL || EPI == EPI_RESID) {
+        float* out = g.out_f32 + (EPI == EPI_PARTIAL ? (size_t)ks * M * N : (size_t)0);
+#pragma unroll
+        for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < T::NI; ++ni) {
+                const int n = n0 + wn * T::WTN + ni * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                    if (m < M) {
+                        const size_t o = (size_t)m * N + n;
+                        out[o] = (EPI == EPI_RESID) ? g.resid[o] + acc[mi][ni][r] : acc[mi][ni][r];
+                    }
+                }
+            }
+    } else {  // EPI_SWIGLU: sub-tile 2j holds gate columns, sub-tile 2j+1 the matching up columns
+        static_assert(EPI != EPI_SWIGLU || T::NI % 2 == 0, "SwiGLU epilogue pairs 32-column sub-tiles");
+        const int half_n = N / 2;
+#pragma unroll
+        for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < T::NI / 2; ++j) {
+                const int col = (n0 + wn * T::WTN) / 2 + j * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                    if (m < M) {
+                        const float gt = acc[mi][2 * j][r], up = acc[mi][2 * j + 1][r];
+                        g.out_bf16[(size_t)m * half_n + col] = f32_to_bf16(gt / (1.f + __expf(-gt)) * up);
+                    }
+                }
+            }
+    }
+}
+
 // WS = number of register sets that stage slabs: WS slabs (A and W chunks alike - loads return in
 // issue order, so a shallower A stream would throttle the W stream) are in flight per workgroup.
 // WS > 1 is for the bandwidth-bound skinny shapes; the K loop is then unrolled WS times so every set
@@ -272,42 +314,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs g) {
         }
     }
 
-    // accumulator layout of the 32x32 MFMA: lane -> column (lane & 31); register r -> row
-    // 8*(r/4) + 4*(lane/32) + r%4
-    if constexpr (EPI == EPI_PARTIAL || EPI == EPI_RESID) {
-        float* out = g.out_f32 + (EPI == EPI_PARTIAL ? (size_t)tc.ks * M * N : (size_t)0);
-#pragma unroll
-        for (int mi = 0; mi < T::MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < T::NI; ++ni) {
-                const int n = n0 + wn * T::WTN + ni * 32 + lrow;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                    if (m < M) {
-                        const size_t o = (size_t)m * N + n;
-                        out[o] = (EPI == EPI_RESID) ? g.resid[o] + acc[mi][ni][r] : acc[mi][ni][r];
-                    }
-                }
-            }
-    } else {  // EPI_SWIGLU: sub-tile 2j holds gate columns, sub-tile 2j+1 the matching up columns
-        static_assert(EPI != EPI_SWIGLU || T::NI % 2 == 0, "SwiGLU epilogue pairs 32-column sub-tiles");
-        const int half_n = N / 2;
-#pragma unroll
-        for (int mi = 0; mi < T::MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < T::NI / 2; ++j) {
-                const int col = (n0 + wn * T::WTN) / 2 + j * 32 + lrow;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * T::WTM + mi * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                    if (m < M) {
-                        const float gt = acc[mi][2 * j][r], up = acc[mi][2 * j + 1][r];
-                        g.out_bf16[(size_t)m * half_n + col] = f32_to_bf16(gt / (1.f + __expf(-gt)) * up);
-                    }
-                }
-            }
-    }
+    store_tile<T, EPI>(acc, g, tc.ks, m0, n0, wm, wn, lrow, lk);
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, int WS = 1>

@@ -27,6 +27,66 @@ extern "C" double laps_lm_boundary_reprefill(double alpha, double beta, double g
     return root > 0.0 ? root : 0.0;
 }
 
+// The same balance with a constant on the memory side: on this GPU a short batch is bounded by streaming the
+// weights once per pass (floor), which the printed T_mem has no term for.  Knee = positive root of
+// alpha L^2 + (2 alpha H + beta - gamma_w) L - (floor + gamma_r H) = 0; floor = 0 gives the printed boundary.
+extern "C" double laps_lm_knee(double alpha, double beta, double gamma_w, double gamma_r, double floor_t, double h) {
+    if (!(alpha > 0.0) || h < 0.0 || floor_t < 0.0 || std::isnan(beta) || std::isnan(gamma_w) || std::isnan(gamma_r) ||
+        std::isnan(floor_t))
+        return NAN;
+    const double b = 2.0 * alpha * h + beta - gamma_w;
+    const double c = floor_t + gamma_r * h;
+    const double disc = b * b + 4.0 * alpha * c;
+    if (disc < 0.0) return 0.0;
+    const double root = (-b + std::sqrt(disc)) / (2.0 * alpha);
+    return root > 0.0 ? root : 0.0;
+}
+
+// Scheduling parameters from a fit.  A batch of up to `knee` padded tokens costs one pass over the weights whatever
+// its shape, so (a) a request longer than the knee is not "short", (b) a latency-oriented graph should not hold more
+// padded tokens than that, (c) requests of other length buckets may share a graph up to that size.
+extern "C" int laps_lm_derive_params(const double* coef, double floor_t, double hist_max, int32_t n_len_buckets,
+                                     const int32_t* len_buckets, int32_t n_depths, const int32_t* depths,
+                                     laps_lm_params* out) {
+    if (!coef || !out || !len_buckets || !depths || n_len_buckets < 1 || n_depths < 1 || hist_max < 0.0) {
+        laps_set_error("lm_derive_params: NULL pointer, empty grid or negative history length");
+        return LAPS_EINVAL;
+    }
+    for (int i = 0; i < n_len_buckets; ++i)
+        if (len_buckets[i] < 1 || (i > 0 && len_buckets[i] <= len_buckets[i - 1])) {
+            laps_set_error("lm_derive_params: length buckets must be positive and strictly ascending");
+            return LAPS_EINVAL;
+        }
+    for (int i = 0; i < n_depths; ++i)
+        if (depths[i] < 1 || (i > 0 && depths[i] <= depths[i - 1])) {
+            laps_set_error("lm_derive_params: depths must be positive and strictly ascending");
+            return LAPS_EINVAL;
+        }
+    const double k0 = laps_lm_knee(coef[0], coef[1], coef[2], coef[3], floor_t, 0.0);
+    const double kh = laps_lm_knee(coef[0], coef[1], coef[2], coef[3], floor_t, hist_max);
+    if (std::isnan(k0) || std::isnan(kh)) {
+        laps_set_error("lm_derive_params: the fit has no knee (alpha must be positive, the floor non-negative)");
+        return LAPS_EINVAL;
+    }
+    const double knee = k0 < kh ? k0 : kh;
+    int32_t sml = len_buckets[0];                       // never below the smallest bucket
+    for (int i = 0; i < n_len_buckets; ++i)
+        if ((double)len_buckets[i] <= knee) sml = len_buckets[i];
+    // largest captured shape (padded tokens) within the knee, but at least one request of the longest short bucket
+    int64_t budget = (int64_t)sml * depths[0];
+    for (int i = 0; i < n_len_buckets && len_buckets[i] <= sml; ++i)
+        for (int j = 0; j < n_depths; ++j) {
+            const int64_t t = (int64_t)len_buckets[i] * depths[j];
+            if ((double)t <= knee && t > budget) budget = t;
+        }
+    out->knee_fresh = k0;
+    out->knee_hist = kh;
+    out->short_max_len = sml;
+    out->short_token_budget = (int32_t)budget;
+    out->fuse_budget = (int32_t)budget;
+    return LAPS_OK;
+}
+
 // Two independent two-parameter least-squares problems through the origin (normal equations):
 //   t_comp ~ alpha * L(L+2H) + beta * L        t_mem ~ gamma_w * L + gamma_r * H
 static int fit2(int n, const double* x1, const double* x2, const double* y, double* c1, double* c2) {

@@ -42,6 +42,18 @@ class DQParams:
                                        # costs one pass over the weights whatever its shape) all waiting short
                                        # requests share the largest needed length bucket: one replay, not three
 
+    @classmethod
+    def from_fit(cls, coef, weight_floor_us: float, hist_max: float, len_buckets=(16, 32, 64),
+                 depths=(1, 2, 4, 8, 16, 32, 64), **kw):
+        """Parameters taken from a run-time fit of the latency model (Section 2.1) instead of constants: the library
+        (laps_lm_derive_params) turns (alpha, beta, gamma_w, gamma_r) and the measured weight-streaming floor into the
+        classification boundary, and the padded-token size up to which a replay costs one pass over the weights - the
+        budget below which waiting requests are fused into one graph and up to which AWD lets other buckets join."""
+        d = api.laps_lm_derive_params(coef, weight_floor_us, hist_max, list(len_buckets), list(depths))
+        buckets = tuple(b for b in len_buckets if b <= d["short_max_len"])
+        return cls(short_max_len=d["short_max_len"], len_buckets=buckets, depths=tuple(depths),
+                   fuse_budget=d["fuse_budget"], merge_below=d["fuse_budget"], **kw)
+
 
 @dataclass
 class DQResult:
@@ -126,15 +138,13 @@ class DualQueue:
                 self.stream.synchronize()
         return us
 
-    def _run_short_batches(self, req_ids):
-        """Plans the waiting short requests and replays one captured graph per planned batch.
+    def _run_short_batches(self, req_ids, fused_len_bucket: int = 0):
+        """Plans the waiting short requests and replays one captured graph per planned batch; with fused_len_bucket
+        (the library's decision, laps_window_poll) every request runs in that one length bucket.
         Returns a list of (request ids, microseconds) per batch."""
         p = self.p
         ids = list(req_ids)
-        buckets = list(p.len_buckets)
-        need = [next(lb for lb in buckets if lb >= self.new_len[r]) for r in ids]
-        if sum(need) < p.merge_below:
-            buckets = [max(need)]
+        buckets = [fused_len_bucket] if fused_len_bucket else list(p.len_buckets)
         plan = api.laps_plan_buckets(min(p.short_max_len, buckets[-1]), buckets, list(p.depths), p.short_token_budget,
                                      p.long_chunk, self.new_len[ids], self.prefix_len[ids])
         assert not plan["longs"]
@@ -212,18 +222,17 @@ class DualQueue:
         t, busy, nxt = 0.0, 0.0, 0
         kinds = {"short_graph": 0, "long_chunk": 0, "short_busy_us": 0.0}
         q_s, q_l = [], []
-        bucket_of = lambda r: next(lb for lb in p.len_buckets if lb >= self.new_len[r])
         while nxt < self.n or q_s or q_l:
             while nxt < self.n and arrival[order[nxt]] <= t:
                 r = order[nxt]
                 (q_l if self.is_long[r] else q_s).append(r)
                 nxt += 1
-            waiting_tokens = sum(bucket_of(r) for r in q_s)
-            due = q_s and (t - arrival[q_s[0]] >= window or waiting_tokens >= p.short_token_budget
-                           or (not q_l and nxt >= self.n))
-            if due:
+            # the dispatch rule (window, budget, nothing else to run) and the fusion rule live in the library
+            dec = api.laps_window_poll(p.len_buckets, window, p.short_token_budget, p.merge_below, t, arrival[q_s],
+                                       self.new_len[q_s], not q_l and nxt >= self.n)
+            if dec["dispatch"]:
                 batch, q_s = q_s, []
-                for ids, us in self._run_short_batches(batch):
+                for ids, us in self._run_short_batches(batch, dec["fused_len_bucket"]):
                     t += us
                     busy += us
                     kinds["short_graph"] += 1
@@ -245,7 +254,7 @@ class DualQueue:
             else:
                 wake = [arrival[order[nxt]]] if nxt < self.n else []
                 if q_s:
-                    wake.append(arrival[q_s[0]] + window)
+                    wake.append(dec["wake_us"])
                 t = max(t, min(wake))
         return DQResult(f"disaggregated(W={window:g}us)", t, busy, kinds["short_graph"] + kinds["long_chunk"], finish,
                         finish - arrival, kinds)

@@ -91,7 +91,8 @@ def collect_samples(ctx: api.LapsCtx, layers, new_lens, hist_lens, reps: int = 3
     return out
 
 
-def fit_and_boundaries(samples, cfg, n_layers: int, comp_min_len: int = 256, report_hist=(0, 1024, 4096, 16384)):
+def fit_and_boundaries(samples, cfg, n_layers: int, comp_min_len: int = 256, report_hist=(0, 1024, 4096, 16384),
+                       len_buckets=(16, 32, 64), depths=(1, 2, 4, 8, 16, 32, 64)):
     comp = [s for s in samples if s["L"] >= comp_min_len]
     L = np.array([s["L"] for s in comp], np.float64)
     H = np.array([s["H"] for s in comp], np.float64)
@@ -125,6 +126,10 @@ def fit_and_boundaries(samples, cfg, n_layers: int, comp_min_len: int = 256, rep
         else:
             knee[str(h)] = api.laps_lm_boundary_reprefill(alpha, beta, gamma_w, gamma_r + floor / h, float(h))
     res["knee_with_weight_floor"] = knee
+    res["knee_library"] = {str(h): api.laps_lm_knee(alpha, beta, gamma_w, gamma_r, floor, float(h)) for h in report_hist}
+    # what the schedule takes from this fit (classification boundary, latency-mode token budget, fusion budget)
+    res["derived"] = api.laps_lm_derive_params((alpha, beta, gamma_w, gamma_r), floor, float(max(report_hist)),
+                                               list(len_buckets), list(depths))
     # arithmetic-intensity reading: projections do 2 flops per parameter per token over 2 bytes per parameter,
     # AI(L) = L flop/byte; the boundary is AI* = P_sustained / B_sustained
     big = max(samples, key=lambda s: (s["L"], -s["H"]))

@@ -135,6 +135,45 @@ int main() {
           std::fabs(coef[3] - 0.25) < 1e-9);
     CHECK(laps_lm_fit(1, L.data(), H.data(), tc.data(), tm.data(), coef) == LAPS_EINVAL);
     CHECK(laps_lm_fit(50, L.data(), L.data(), tc.data(), tm.data(), coef) == LAPS_EINVAL);
+    // knee with a weight-streaming floor and the parameters derived from a fit
+    CHECK(std::fabs(laps_lm_knee(1.0, 2.0, 10.0, 3.0, 9.0, 4.0) - std::sqrt(21.0)) < 1e-12);
+    CHECK(std::isnan(laps_lm_knee(0.0, 1.0, 1.0, 1.0, 1.0, 0.0)));
+    {
+        const int32_t lb[3] = {16, 32, 64}, dp[7] = {1, 2, 4, 8, 16, 32, 64};
+        const double c1[4] = {1.0, 0.0, 0.0, 0.0};
+        laps_lm_params prm;
+        CHECK(laps_lm_derive_params(c1, 200.0 * 200.0, 0.0, 3, lb, 7, dp, &prm) == LAPS_OK);
+        CHECK(prm.short_max_len == 64 && prm.short_token_budget == 128 && prm.fuse_budget == 128);
+        CHECK(laps_lm_derive_params(c1, 10.0 * 10.0, 0.0, 3, lb, 7, dp, &prm) == LAPS_OK && prm.short_max_len == 16);
+        CHECK(laps_lm_derive_params(c1, 1.0, -1.0, 3, lb, 7, dp, &prm) == LAPS_EINVAL);
+        CHECK(laps_lm_derive_params(c1, 1.0, 0.0, 0, lb, 7, dp, &prm) == LAPS_EINVAL);
+    }
+    // fixed-window dispatch over random queues: every output is written, grids and lengths are only read in range
+    for (int it = 0; it < 2000; ++it) {
+        const int32_t lb[3] = {16, 32, 64};
+        const int n = (int)(rng() % 40);
+        std::vector<double> arr(n);
+        std::vector<int32_t> nl(n);
+        double t = 0;
+        for (int i = 0; i < n; ++i) {
+            t += (double)(rng() % 300);
+            arr[i] = t;
+            nl[i] = 1 + (int32_t)(rng() % 64);
+        }
+        laps_window_params wp = {3, lb, (double)(rng() % 2000), (int64_t)(1 + rng() % 2048), (int64_t)(rng() % 300)};
+        int32_t action = -1, fused = -1;
+        int64_t padded = -1;
+        double wake = -1;
+        CHECK(laps_window_poll(&wp, t + (double)(rng() % 500), n, arr.data(), nl.data(), (int32_t)(rng() % 2), &action, &fused,
+                               &padded, &wake) == LAPS_OK);
+        CHECK((action == LAPS_AWD_WAIT || action == LAPS_AWD_DISPATCH) && padded >= 16 * n && padded <= 64 * n);
+        CHECK(fused == 0 || fused == 16 || fused == 32 || fused == 64);
+        if (n == 0) CHECK(action == LAPS_AWD_WAIT && std::isinf(wake));
+        if (n > 0) {
+            nl[n - 1] = 65;
+            CHECK(laps_window_poll(&wp, t, n, arr.data(), nl.data(), 0, &action, &fused, &padded, &wake) == LAPS_EINVAL);
+        }
+    }
     printf("OK\n");
     return 0;
 }

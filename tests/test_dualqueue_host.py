@@ -145,3 +145,43 @@ def test_awd_loop_on_the_step_model_serves_everything_within_the_captured_grid()
     # head-of-line cap: no short request waits longer than T_max plus the long chunk that may be in flight and the replay
     short = new_len <= 64
     assert res.latency_us[short].max() <= 25_000.0 + (100.0 + 4.0 * 2048) + (900.0 + 0.5 * 512) + 1e-6
+
+
+def test_schedule_parameters_follow_the_runtime_fit():
+    """Section 2.1 "runtime fitting", closed into the schedule: samples (T_comp, T_mem, L, H) planted from two
+    different machines go through the library's fit and parameter derivation, and the dual-queue parameters move with
+    them - the classification boundary, the bucket grid in use, the fusion budget - and with them what the step
+    loop does with the same requests."""
+    from paper_2601_11589_amd import api
+    rng = np.random.default_rng(5)
+    L = rng.integers(1, 2049, 120).astype(float)
+    H = rng.choice([0.0, 1024.0, 4096.0], 120)
+    grid = dict(len_buckets=(8, 16, 32, 64, 128, 256), depths=(1, 2, 4, 8, 16, 32, 64))
+
+    def params_for(alpha, beta, gamma_w, gamma_r, floor_us):
+        tc = alpha * L * (L + 2 * H) + beta * L
+        tm = gamma_w * L + gamma_r * H
+        coef = api.laps_lm_fit(L, H, tc * (1 + 0.01 * rng.standard_normal(120)), tm * (1 + 0.01 * rng.standard_normal(120)))
+        assert coef == pytest.approx((alpha, beta, gamma_w, gamma_r), rel=0.05)
+        return dualqueue.DQParams.from_fit(coef, floor_us, 4096.0, **grid), coef
+
+    # machine A: the figures measured on MI355X (microseconds, 4 layers): the knee lies near 200 padded tokens
+    pa, ca = params_for(5.6e-5, 3.6, 0.1, 0.02, 700.0)
+    assert 150 < api.laps_lm_knee(*ca, 700.0, 4096.0) < api.laps_lm_knee(*ca, 700.0, 0.0) < 250
+    assert (pa.short_max_len, pa.fuse_budget, pa.merge_below) == (128, 128, 128) and pa.len_buckets == (8, 16, 32, 64, 128)
+    # machine B: four times the bandwidth for the same arithmetic (floor 175 us): the knee drops to ~49 tokens for a
+    # fresh prompt (175 / (beta - gamma_w)); with history the cache read adds to the memory side and it is a little higher
+    pb, cb = params_for(5.6e-5, 3.6, 0.1, 0.02, 175.0)
+    assert 32 < api.laps_lm_knee(*cb, 175.0, 0.0) < 64 and api.laps_lm_knee(*cb, 175.0, 4096.0) > api.laps_lm_knee(*cb, 175.0, 0.0)
+    assert (pb.short_max_len, pb.fuse_budget, pb.merge_below) == (32, 32, 32) and pb.len_buckets == (8, 16, 32)
+    # the same five requests, all waiting at t = 0: under A all but the 300-token one are short and (8+16+64+128 = 216
+    # padded tokens, not below 128) run bucket by bucket; under B only the 8- and 12-token requests are short, and being
+    # 8 + 16 = 24 < 32 padded tokens they are fused into one 16-token graph
+    new_len = [8, 12, 50, 100, 300]
+    for prm, n_long, graphs in ((pa, 1, [(8, 1), (16, 1), (64, 1), (128, 1)]), (pb, 3, [(16, 2)])):
+        model = LinearSteps()
+        dq = host_queue(new_len, prm, model)
+        assert int(dq.is_long.sum()) == n_long
+        res = dq.run_disaggregated(np.zeros(5), window_us=0.0)
+        assert np.all(res.finish_us > 0)
+        assert sorted((e[1], e[2]) for e in model.log if e[0] == "graph") == graphs

@@ -130,11 +130,11 @@ def test_planner_under_address_and_ub_sanitizers(repo_root, tmp_path):
 
 
 def test_host_objects_under_address_and_ub_sanitizers(repo_root, tmp_path):
-    """Host code only: the AWD state machine, the pool controller and the latency-model helpers, driven by seeded
+    """Host code only: the AWD state machine, the pool controller, the latency-model helpers and the fixed-window rule, driven by seeded
     random event loops, built with -fsanitize=address,undefined."""
     exe = str(tmp_path / "host_san")
     csrc = os.path.join(repo_root, "paper_2601_11589_amd", "csrc")
-    src = [os.path.join(csrc, f) for f in ("awd.cpp", "pool_ctrl.cpp", "latency_model.cpp")] + \
+    src = [os.path.join(csrc, f) for f in ("awd.cpp", "pool_ctrl.cpp", "latency_model.cpp", "window.cpp")] + \
           [os.path.join(repo_root, "tests", "host_objects_sanitize_driver.cpp")]
     build = subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
                             "-o", exe] + src, capture_output=True, text=True)
