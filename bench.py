@@ -556,8 +556,8 @@ def main():
     ap.add_argument("--loads", type=str, default="0.7",
                     help="dual queue: Poisson arrival rates as fractions of the unified back-to-back service rate")
     ap.add_argument("--long-steps", type=int, default=2)
-    ap.add_argument("--reprefill-token-max", action="store_true",
-                    help="also run the re-prefill workload with token budget 4096")
+    ap.add_argument("--no-reprefill-token-max", action="store_true",
+                    help="skip the token-budget-4096 variant of the re-prefill workload")
     ap.add_argument("--detail-file", type=str, default="bench_detail.json",
                     help="file under gpurun_out/ that receives the full record (per-shape tables, samples, trajectories)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -651,7 +651,7 @@ def main():
         line["reprefill"] = {"tokens_per_s": rp["tokens_per_s"], "latency_ms_p50": rp["latency_ms_p50"],
                              "latency_ms_p90": rp["latency_ms_p90"], "attn_kv_GBps": rp["attention"]["kv_GBps"],
                              "attn_us_per_layer": rp["attention"]["us_per_layer_batch"]}
-        if args.reprefill_token_max:
+        if not args.no_reprefill_token_max:
             log("[bench] leg: re-prefill, token-max")
             rp2 = run_short(ctx, layers, cfg, 4096, max(2, args.steps // 2), 1, True, "re-prefill-4096", config=3)
             rp2.pop("gemm")

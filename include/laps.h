@@ -241,9 +241,12 @@ int laps_graph_capture(laps_ctx* ctx, const laps_layer_weights* w, int32_t len_b
  * device pointers: seq_len_dev, prefix_len_dev [n_real] (a length is clamped to [0, len_bucket] on
  * the device); page_table_dev [n_real, max_pages] with row stride max_pages; x_rows_dev fp32
  * [n_rows, hidden], the sequences' rows packed in slot order, n_rows = the sum of the lengths
- * (0 <= n_rows <= depth*len_bucket, else LAPS_EINVAL; x_rows_dev may be NULL when n_rows is 0, e.g.
- * when the caller wrote laps_graph_input() in place).  Enqueues one metadata kernel and
- * device-to-device copies. */
+ * (0 <= n_rows <= depth*len_bucket, else LAPS_EINVAL).  x_rows_dev may be NULL with n_rows 0 when the caller
+ * has written laps_graph_input() in place: those rows must then be complete before this call, which reads them.
+ * Enqueues two kernels that prepare everything a replay needs besides the layers themselves: lengths, row
+ * offsets and the attention's work-item table (one workgroup), then per row the token's position and cache slot,
+ * the copy of its input, its RMSNorm with the first layer's gain, and the page-table copy.  A replay therefore
+ * starts with the first projection; replaying again without staging repeats the same batch. */
 int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* seq_len_dev, const int32_t* prefix_len_dev,
                      const int32_t* page_table_dev, const float* x_rows_dev, int32_t n_rows, void* stream);
 int laps_graph_replay(laps_graph* g, void* stream);

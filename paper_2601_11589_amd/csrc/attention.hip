@@ -39,30 +39,7 @@ __global__ __launch_bounds__(256) void attn_sched_kernel(const int* __restrict__
                                                           int* __restrict__ item_seq, int max_items) {
     __shared__ int buf[256];
     __shared__ int carry;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
-    for (int base = 0; base < n_seq; base += 256) {
-        const int i = base + threadIdx.x;
-        const int v = (i < n_seq) ? (new_len[i] * group + rows_per_wg - 1) / rows_per_wg : 0;
-        buf[threadIdx.x] = v;
-        __syncthreads();
-        for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele scan
-            const int add = (threadIdx.x >= o) ? buf[threadIdx.x - o] : 0;
-            __syncthreads();
-            buf[threadIdx.x] += add;
-            __syncthreads();
-        }
-        const int c = carry;
-        if (i < n_seq) {
-            const int first = c + buf[threadIdx.x] - v;
-            tile_start[i] = first;
-            for (int k = 0; k < v && first + k < max_items; ++k) item_seq[first + k] = i;   // bound: lengths that disagree with the row offsets must not write past the table
-        }
-        __syncthreads();
-        if (threadIdx.x == 255) carry = c + buf[255];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) tile_start[n_seq] = carry;
+    laps_dev_attn_sched(new_len, n_seq, group, rows_per_wg, tile_start, item_seq, max_items, buf, &carry);
 }
 
 // NW waves per workgroup, one 32-row query tile per wave: rows per workgroup = 32 * NW.  With NW = 8

@@ -279,10 +279,12 @@ static int run_gemm(laps_ctx* c, int cls, bool capturing, const bf16_t* a, const
     return laps_gemm_launch(p, a, w, m, n, k, out_f32, resid, out_bf16, row_live, s);
 }
 
-// Runs layers [0, n_layers) of `w`.  Token metadata (prep) is computed once.
+// Runs layers [0, n_layers) of `w`.  Token metadata (prep) is computed once.  r0_staged: the first layer's normed
+// rows, with token metadata and the attention's work-item table already in the workspace (a captured graph:
+// laps_graph_stage prepared them, so that a replay starts with the first projection).
 static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, const BatchDesc& b, void* const* k_pools,
                       void* const* v_pools, const float* x_in, float* x_out, unsigned char* ws, bool capturing,
-                      hipStream_t s) {
+                      hipStream_t s, const bf16_t* r0_staged = nullptr) {
     const laps_model_cfg& cf = c->cfg;
     const int M = b.n_tokens, d = cf.hidden, hd = cf.head_dim;
     const int qd = cf.n_q_heads * hd, qkv = qd + 2 * cf.n_kv_heads * hd, I = cf.intermediate;
@@ -299,18 +301,20 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
     float* x_mid = reinterpret_cast<float*>(ws + L.x_mid);
     float* partial = reinterpret_cast<float*>(ws + L.partial);
 
-    {
-        ProfScope ps(c, s, LAPS_K_PREP, capturing);
-        LAPS_TRY(laps_launch_prep(M, b.n_seq, b.row_start, b.seq_len, b.prefix_len, b.page_table, b.max_pages,
-                                  c->pool_pages, new_len, tok_pos, tok_slot, s));
-    }
-    {
-        ProfScope ps(c, s, LAPS_K_PREP, capturing);
-        LAPS_TRY(laps_launch_attn_sched(new_len, b.n_seq, M, b.max_pages, tile_start, item_seq, cf.n_q_heads, cf.n_kv_heads, s));
-    }
-    {
-        ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
-        LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, tok_pos, s));
+    if (r0_staged == nullptr) {
+        {
+            ProfScope ps(c, s, LAPS_K_PREP, capturing);
+            LAPS_TRY(laps_launch_prep(M, b.n_seq, b.row_start, b.seq_len, b.prefix_len, b.page_table, b.max_pages,
+                                      c->pool_pages, new_len, tok_pos, tok_slot, s));
+        }
+        {
+            ProfScope ps(c, s, LAPS_K_PREP, capturing);
+            LAPS_TRY(laps_launch_attn_sched(new_len, b.n_seq, M, b.max_pages, tile_start, item_seq, cf.n_q_heads, cf.n_kv_heads, s));
+        }
+        {
+            ProfScope ps(c, s, LAPS_K_RMSNORM, capturing);
+            LAPS_TRY(laps_launch_rmsnorm(x_in, static_cast<const bf16_t*>(w[0].ln1_w), r, M, d, cf.rms_eps, tok_pos, s));
+        }
     }
     for (int l = 0; l < n_layers; ++l) {
         const laps_layer_weights& lw = w[l];
@@ -319,7 +323,8 @@ static int run_layers(laps_ctx* c, const laps_layer_weights* w, int n_layers, co
         bf16_t* vp = static_cast<bf16_t*>(v_pools[l]);
         GemmPlan gp;
         // q, k, v: GEMM -> K-slice sums -> bias + RoPE + KV append
-        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r, static_cast<const bf16_t*>(lw.w_qkv), M, qkv, d, EPI_PARTIAL,
+        const bf16_t* r_in = (l == 0 && r0_staged != nullptr) ? r0_staged : r;
+        LAPS_TRY(run_gemm(c, LAPS_K_GEMM_QKV, capturing, r_in, static_cast<const bf16_t*>(lw.w_qkv), M, qkv, d, EPI_PARTIAL,
                           partial, nullptr, nullptr, nullptr, tok_pos, &gp, s));
         {
             ProfScope ps(c, s, LAPS_K_EPI_QKV, capturing);
@@ -670,10 +675,49 @@ struct laps_graph {
     size_t block_bytes;
     float *x_in, *x_out;
     int *row_start, *seq_len, *prefix_len, *page_table;
+    bf16_t* r0;               // first layer's normed rows, written when a batch is staged
+    const bf16_t* ln1_first;  // the first layer's RMSNorm gain
     unsigned char* ws;
     hipGraph_t graph;
     hipGraphExec_t exec;
 };
+
+// The two staging launches of a graph (see StageArgs): everything a replay needs besides the layers themselves.
+static int graph_stage_launch(laps_graph* g, int n_real, const int* seq_len, const int* prefix_len, const int* page_table,
+                              const float* x_rows, int n_rows, hipStream_t s) {
+    const laps_model_cfg& cf = g->ctx->cfg;
+    const int M = g->depth * g->len_bucket;
+    const WsLayout L = ws_layout(cf, M, g->depth);
+    StageArgs a;
+    a.seq_len = seq_len;
+    a.prefix_len = prefix_len;
+    a.page_table = page_table;
+    a.x_rows = x_rows;
+    a.n_real = n_real;
+    a.n_rows = n_rows;
+    a.depth = g->depth;
+    a.len_bucket = g->len_bucket;
+    a.max_pages = g->max_pages;
+    a.n_pool_pages = g->ctx->pool_pages;
+    a.group = cf.n_q_heads / cf.n_kv_heads;
+    int n_split = 0, min_tiles = 0;
+    laps_attn_plan(g->depth, M, a.group, cf.n_kv_heads, g->max_pages, &a.rows_per_wg, &a.max_items, &n_split, &min_tiles);
+    a.seq_len_out = g->seq_len;
+    a.prefix_out = g->prefix_len;
+    a.row_start_out = g->row_start;
+    a.page_table_out = g->page_table;
+    a.new_len_out = reinterpret_cast<int*>(g->ws + L.new_len);
+    a.tok_pos = reinterpret_cast<int*>(g->ws + L.tok_pos);
+    a.tok_slot = reinterpret_cast<int*>(g->ws + L.tok_slot);
+    a.tile_start = reinterpret_cast<int*>(g->ws + L.tile_start);
+    a.item_seq = reinterpret_cast<int*>(g->ws + L.item_seq);
+    a.x_in = g->x_in;
+    a.ln_w = g->ln1_first;
+    a.r0 = g->r0;
+    a.d = cf.hidden;
+    a.eps = cf.rms_eps;
+    return laps_launch_stage(a, s);
+}
 
 extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int32_t len_bucket, int32_t depth,
                                   int32_t max_pages, void* const* k_pools, void* const* v_pools, void* stream,
@@ -714,6 +758,7 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
     const size_t o_sl = o;   o += align256((size_t)depth * 4);
     const size_t o_pl = o;   o += align256((size_t)depth * 4);
     const size_t o_pt = o;   o += align256((size_t)depth * max_pages * 4);
+    const size_t o_r0 = o;   o += align256(M * d * 2);
     const size_t o_ws = o;   o += ws_bytes;
     g->block_bytes = o;
     auto fail = [&](int rc) {
@@ -735,6 +780,8 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
     g->seq_len = reinterpret_cast<int*>(g->block + o_sl);
     g->prefix_len = reinterpret_cast<int*>(g->block + o_pl);
     g->page_table = reinterpret_cast<int*>(g->block + o_pt);
+    g->r0 = reinterpret_cast<bf16_t*>(g->block + o_r0);
+    g->ln1_first = static_cast<const bf16_t*>(w[0].ln1_w);
     g->ws = g->block + o_ws;
     // all slots empty (every row offset 0, every length 0), inputs zero; done before capture, so a plain
     // memset is fine here
@@ -743,8 +790,10 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
         return fail(LAPS_EHIP);
     }
     const BatchDesc b{depth, (int)M, g->row_start, g->seq_len, g->prefix_len, g->page_table, max_pages};
+    // every slot empty: token metadata and work-item table of an empty batch, as the captured kernels expect to find them
+    int rc = graph_stage_launch(g, 0, nullptr, nullptr, nullptr, nullptr, 0, s);
     // warm-up pass: loads code objects and sets kernel attributes outside the capture
-    int rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s);
+    if (rc == LAPS_OK) rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s, g->r0);
     if (rc == LAPS_OK && (e = hipStreamSynchronize(s)) != hipSuccess) {
         laps_set_error("graph_capture: warm-up failed: %s", hipGetErrorString(e));
         rc = LAPS_EHIP;
@@ -754,7 +803,7 @@ extern "C" int laps_graph_capture(laps_ctx* c, const laps_layer_weights* w, int3
         laps_set_error("graph_capture: hipStreamBeginCapture failed: %s", hipGetErrorString(e));
         return fail(LAPS_EHIP);
     }
-    rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s);
+    rc = run_layers(c, w, nl, b, k_pools, v_pools, g->x_in, g->x_out, g->ws, true, s, g->r0);
     e = hipStreamEndCapture(s, &g->graph);
     if (rc != LAPS_OK) return fail(rc);
     if (e != hipSuccess || !g->graph) {
@@ -780,13 +829,7 @@ extern "C" int laps_graph_stage(laps_graph* g, int32_t n_real, const int32_t* se
         laps_set_error("graph_stage: %d input rows do not fit the graph's %d rows", n_rows, g->depth * g->len_bucket);
         return LAPS_EINVAL;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    LAPS_TRY(laps_launch_stage_meta(seq_len, prefix_len, n_real, g->depth, g->len_bucket, g->seq_len, g->prefix_len,
-                                    g->row_start, s));
-    LAPS_TRY(laps_launch_copy_i32(g->page_table, page_table, n_real * g->max_pages, 0, g->depth * g->max_pages, s));
-    if (n_rows > 0)
-        LAPS_HIP(hipMemcpyAsync(g->x_in, x_rows, (size_t)n_rows * g->ctx->cfg.hidden * 4, hipMemcpyDeviceToDevice, s));
-    return LAPS_OK;
+    return graph_stage_launch(g, n_real, seq_len, prefix_len, page_table, x_rows, n_rows, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int laps_graph_replay(laps_graph* g, void* stream) {

@@ -32,20 +32,12 @@ __global__ void rope_table_kernel(float2* table, int max_pos, int half, double t
 }
 
 // ------------------------------------------------------------------ token metadata
-// One thread per row: owning sequence by binary search over row_start, then absolute position and
-// KV slot (page * 16 + offset) of the token; -1 for padding rows.
-__global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_start, const int* __restrict__ seq_len,
-                            const int* __restrict__ prefix_len, const int* __restrict__ page_table, int max_pages,
-                            int n_pool_pages, int* __restrict__ new_len_out, int* __restrict__ tok_pos,
-                            int* __restrict__ tok_slot) {
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    if (row < n_seq) {
-        const int cap = row_start[row + 1] - row_start[row];
-        int l = seq_len ? seq_len[row] : cap;
-        l = l > cap ? cap : l;
-        new_len_out[row] = l < 0 ? 0 : l;
-    }
-    if (row >= n_rows) return;
+// Owning sequence of a row by binary search over row_start, then absolute position and KV slot
+// (page * 16 + offset) of the token; -1 for padding rows.
+__device__ __forceinline__ void token_meta(int row, int n_seq, const int* __restrict__ row_start,
+                                           const int* __restrict__ seq_len, const int* __restrict__ prefix_len,
+                                           const int* __restrict__ page_table, int max_pages, int n_pool_pages, int* pos_out,
+                                           int* slot_out) {
     int lo = 0, hi = n_seq;  // find s with row_start[s] <= row < row_start[s+1]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -65,25 +57,40 @@ __global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_s
         const int page = pi < max_pages ? page_table[(size_t)s * max_pages + pi] : -1;
         slot = (page >= 0 && page < n_pool_pages) ? page * LAPS_PAGE + pos % LAPS_PAGE : -1;
     }
+    *pos_out = pos;
+    *slot_out = slot;
+}
+
+// One thread per row (and per sequence for the clamped lengths).
+__global__ void prep_kernel(int n_rows, int n_seq, const int* __restrict__ row_start, const int* __restrict__ seq_len,
+                            const int* __restrict__ prefix_len, const int* __restrict__ page_table, int max_pages,
+                            int n_pool_pages, int* __restrict__ new_len_out, int* __restrict__ tok_pos,
+                            int* __restrict__ tok_slot) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row < n_seq) {
+        const int cap = row_start[row + 1] - row_start[row];
+        int l = seq_len ? seq_len[row] : cap;
+        l = l > cap ? cap : l;
+        new_len_out[row] = l < 0 ? 0 : l;
+    }
+    if (row >= n_rows) return;
+    int pos, slot;
+    token_meta(row, n_seq, row_start, seq_len, prefix_len, page_table, max_pages, n_pool_pages, &pos, &slot);
     tok_pos[row] = pos;
     tok_slot[row] = slot;
 }
 
 // ------------------------------------------------------------------ RMSNorm: fp32 row -> bf16 row
-__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x,
-                                                               const bf16_t* __restrict__ w, bf16_t* __restrict__ out,
-                                                               int d, float eps, const int* __restrict__ row_live) {
-    __shared__ float red[ROW_THREADS / 64];
-    const size_t row = blockIdx.x;
-    if (row_live && row_live[row] < 0) return;  // padding row: nothing reads its output
-    const f32x4* xr = reinterpret_cast<const f32x4*>(x + row * d);
+// One row with ROW_THREADS threads; xr may be any fp32 row of d values, red holds ROW_THREADS / 64 floats of LDS.
+__device__ __forceinline__ void rmsnorm_row(const f32x4* __restrict__ xr, const bf16_t* __restrict__ w,
+                                            bf16_t* __restrict__ out_row, int d, float eps, float* red) {
     float ss = 0.f;
     for (int i = threadIdx.x; i < d / 4; i += ROW_THREADS) {
         const f32x4 v = xr[i];
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     const float inv = rsqrtf(block_sum(ss, red) / (float)d + eps);
-    u32x2* orow = reinterpret_cast<u32x2*>(out + row * d);
+    u32x2* orow = reinterpret_cast<u32x2*>(out_row);
     const u32x2* wr = reinterpret_cast<const u32x2*>(w);
     for (int i = threadIdx.x; i < d / 4; i += ROW_THREADS) {
         const f32x4 v = xr[i];
@@ -93,6 +100,15 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __res
         o.y = pack_bf16x2(v.z * inv * __uint_as_float(g.y << 16), v.w * inv * __uint_as_float(g.y & 0xffff0000u));
         orow[i] = o;
     }
+}
+
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x,
+                                                               const bf16_t* __restrict__ w, bf16_t* __restrict__ out,
+                                                               int d, float eps, const int* __restrict__ row_live) {
+    __shared__ float red[ROW_THREADS / 64];
+    const size_t row = blockIdx.x;
+    if (row_live && row_live[row] < 0) return;  // padding row: nothing reads its output
+    rmsnorm_row(reinterpret_cast<const f32x4*>(x + row * d), w, out + row * d, d, eps, red);
 }
 
 // ------------------------------------------------------------------ sum K slices + residual (+ RMSNorm)
@@ -318,31 +334,22 @@ __global__ void kv_move_kernel(int n_seq, int n_tokens, const int* __restrict__ 
     }
 }
 
-// dst[i] = src[i] for i < n; dst[i] = fill_value for n <= i < total (stages a graph's page table without
-// memset nodes)
-__global__ void copy_fill_i32_kernel(int* __restrict__ dst, const int* __restrict__ src, int n, int fill_value, int total) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    dst[i] = (i < n) ? src[i] : fill_value;
-}
-
 // Metadata of one captured bucket, from what the caller staged for its first n_real slots: lengths
 // clamped to [0, len_bucket], prefix lengths to >= 0, the other slots empty, and the sequences packed
 // one after the other (row_start = running sum of the clamped lengths, so the total never exceeds the
-// graph's depth * len_bucket rows whatever the caller's arrays hold).  One workgroup; thread t owns a
-// run of consecutive slots.
+// graph's depth * len_bucket rows whatever the caller's arrays hold); then the attention's work-item table
+// for those lengths.  One workgroup; thread t owns a run of consecutive slots.
 constexpr int META_THREADS = 256;
-__global__ __launch_bounds__(META_THREADS) void stage_meta_kernel(const int* __restrict__ seq_len,
-                                                                  const int* __restrict__ prefix_len, int n_real,
-                                                                  int depth, int len_bucket, int* __restrict__ seq_len_out,
-                                                                  int* __restrict__ prefix_out, int* __restrict__ row_start_out) {
+__global__ __launch_bounds__(META_THREADS) void stage_meta_kernel(const StageArgs a) {
     __shared__ int sums[META_THREADS];
+    __shared__ int carry;
     const int t = threadIdx.x;
+    const int depth = a.depth;
     const int per = (depth + META_THREADS - 1) / META_THREADS;
     const int lo = t * per, hi = (lo + per < depth) ? lo + per : depth;
     auto len_of = [&](int i) {
-        int l = i < n_real ? seq_len[i] : 0;
-        l = l > len_bucket ? len_bucket : l;
+        int l = i < a.n_real ? a.seq_len[i] : 0;
+        l = l > a.len_bucket ? a.len_bucket : l;
         return l < 0 ? 0 : l;
     };
     int mine = 0;
@@ -358,21 +365,55 @@ __global__ __launch_bounds__(META_THREADS) void stage_meta_kernel(const int* __r
     int run = sums[t] - mine;
     for (int i = lo; i < hi; ++i) {
         const int l = len_of(i);
-        row_start_out[i] = run;
-        seq_len_out[i] = l;
-        const int pf = i < n_real ? prefix_len[i] : 0;
-        prefix_out[i] = pf < 0 ? 0 : pf;
+        a.row_start_out[i] = run;
+        a.seq_len_out[i] = l;
+        a.new_len_out[i] = l;
+        const int pf = i < a.n_real ? a.prefix_len[i] : 0;
+        a.prefix_out[i] = pf < 0 ? 0 : pf;
         run += l;
     }
-    if (t == META_THREADS - 1) row_start_out[depth] = sums[t];
+    if (t == META_THREADS - 1) a.row_start_out[depth] = sums[t];
+    __syncthreads();   // the lengths written above are read below by other threads of this workgroup
+    laps_dev_attn_sched(a.new_len_out, depth, a.group, a.rows_per_wg, a.tile_start, a.item_seq, a.max_items, sums, &carry);
+}
+
+// One workgroup per graph row; see StageArgs.  Runs after stage_meta_kernel on the same stream.
+__global__ __launch_bounds__(ROW_THREADS) void stage_rows_kernel(const StageArgs a) {
+    __shared__ float red[ROW_THREADS / 64];
+    __shared__ int live;
+    const int row = blockIdx.x;
+    {   // this workgroup's share of the page-table copy
+        const int total = a.depth * a.max_pages, n_src = a.n_real * a.max_pages;
+        const int chunk = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+        const int end = (row + 1) * chunk < total ? (row + 1) * chunk : total;
+        for (int i = row * chunk + threadIdx.x; i < end; i += ROW_THREADS) a.page_table_out[i] = i < n_src ? a.page_table[i] : 0;
+    }
+    if (threadIdx.x == 0) {
+        int pos, slot;   // lengths, prefixes and row offsets as clamped by stage_meta_kernel; page ids from the caller's table
+        token_meta(row, a.depth, a.row_start_out, a.seq_len_out, a.prefix_out, a.page_table, a.max_pages, a.n_pool_pages,
+                   &pos, &slot);
+        a.tok_pos[row] = pos;
+        a.tok_slot[row] = slot;
+        live = pos >= 0;
+    }
+    const f32x4* src = reinterpret_cast<const f32x4*>(a.x_in + (size_t)row * a.d);
+    if (a.x_rows != nullptr && row < a.n_rows) {
+        src = reinterpret_cast<const f32x4*>(a.x_rows + (size_t)row * a.d);
+        f32x4* dst = reinterpret_cast<f32x4*>(a.x_in + (size_t)row * a.d);
+        if (src != dst)
+            for (int i = threadIdx.x; i < a.d / 4; i += ROW_THREADS) dst[i] = src[i];
+    }
+    __syncthreads();
+    if (!live) return;   // padding row: nothing reads its normed row
+    rmsnorm_row(src, a.ln_w, a.r0 + (size_t)row * a.d, a.d, a.eps, red);
 }
 
 }  // namespace
 
-int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
-                           int* seq_len_out, int* prefix_out, int* row_start_out, hipStream_t s) {
-    hipLaunchKernelGGL(stage_meta_kernel, dim3(1), dim3(META_THREADS), 0, s, seq_len, prefix_len, n_real, depth,
-                       len_bucket, seq_len_out, prefix_out, row_start_out);
+int laps_launch_stage(const StageArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(stage_meta_kernel, dim3(1), dim3(META_THREADS), 0, s, a);
+    LAPS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(stage_rows_kernel, dim3(a.depth * a.len_bucket), dim3(ROW_THREADS), 0, s, a);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }
@@ -461,13 +502,6 @@ int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, co
     else
         hipLaunchKernelGGL(kv_move_kernel<false>, dim3(n_tokens), dim3(256), 0, s, n_seq, n_tokens, cu, start_pos,
                            page_table, max_pages, k_tok, v_tok, k_pool, v_pool, n_kv, hd, n_pool_pages);
-    LAPS_LAUNCH_CHECK();
-    return LAPS_OK;
-}
-
-int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_value, int total, hipStream_t s) {
-    if (total <= 0) return LAPS_OK;
-    hipLaunchKernelGGL(copy_fill_i32_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dst, src, n, fill_value, total);
     LAPS_LAUNCH_CHECK();
     return LAPS_OK;
 }

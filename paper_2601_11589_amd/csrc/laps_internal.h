@@ -84,12 +84,60 @@ int laps_launch_pack_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* dst, in
 int laps_launch_kv_move(bool scatter, int n_seq, int n_tokens, const int* cu, const int* start_pos,
                         const int* page_table, int max_pages, bf16_t* k_tok, bf16_t* v_tok, bf16_t* k_pool,
                         bf16_t* v_pool, int n_kv, int hd, int n_pool_pages, hipStream_t s);
-// Graph staging: clamped lengths / prefixes of `depth` slots (the first n_real from the caller's device arrays, the
-// rest empty) and packed row offsets row_start_out[depth + 1].
-int laps_launch_stage_meta(const int* seq_len, const int* prefix_len, int n_real, int depth, int len_bucket,
-                           int* seq_len_out, int* prefix_out, int* row_start_out, hipStream_t s);
-// dst[i] = src[i] for i < n, fill_value for n <= i < total
-int laps_launch_copy_i32(int* dst, const int* src, int n, int fill_value, int total, hipStream_t s);
+// Graph staging, two launches that leave a captured stack nothing to prepare:
+// (1) one workgroup: clamped lengths / prefixes of `depth` slots (the first n_real from the caller's device arrays,
+//     the rest empty), packed row offsets row_start_out[depth + 1], and the attention's work-item table for them;
+// (2) one workgroup per graph row: token position and cache slot (as laps_launch_prep), the row's input copied from
+//     x_rows (rows below n_rows; NULL: the graph's input rows are used as they are) into x_in, its RMSNorm with the
+//     first layer's gain into r0, and a share of the page-table copy (entries past n_real rows become 0).
+struct StageArgs {
+    const int *seq_len, *prefix_len, *page_table;   // caller's device arrays: [n_real], [n_real], [n_real][max_pages]
+    const float* x_rows;                            // caller's packed input rows or NULL
+    int n_real, n_rows, depth, len_bucket, max_pages, n_pool_pages;
+    int group, rows_per_wg, max_items;              // attention blocking of the graph's shape
+    int *seq_len_out, *prefix_out, *row_start_out, *page_table_out;   // the graph's staging block
+    int *new_len_out, *tok_pos, *tok_slot, *tile_start, *item_seq;    // the graph's workspace
+    float* x_in;
+    const bf16_t* ln_w;
+    bf16_t* r0;
+    int d;
+    float eps;
+};
+int laps_launch_stage(const StageArgs& a, hipStream_t s);
+
+// Work-item table of the attention for one batch: per-sequence number of query-row blocks, their exclusive prefix
+// sum (tile_start[n_seq + 1]) and the sequence of every work item.  Runs in ONE workgroup of 256 threads; buf holds
+// 256 ints and carry one int of LDS.  Shared by the stand-alone scheduling kernel and the staging kernel of graphs.
+static __device__ __forceinline__ void laps_dev_attn_sched(const int* __restrict__ new_len, int n_seq, int group,
+                                                           int rows_per_wg, int* __restrict__ tile_start,
+                                                           int* __restrict__ item_seq, int max_items, int* buf,
+                                                           int* carry) {
+    if (threadIdx.x == 0) *carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_seq; base += 256) {
+        const int i = base + threadIdx.x;
+        const int v = (i < n_seq) ? (new_len[i] * group + rows_per_wg - 1) / rows_per_wg : 0;
+        buf[threadIdx.x] = v;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele scan
+            const int add = (threadIdx.x >= o) ? buf[threadIdx.x - o] : 0;
+            __syncthreads();
+            buf[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int c = *carry;
+        if (i < n_seq) {
+            const int first = c + buf[threadIdx.x] - v;
+            tile_start[i] = first;
+            // bound: lengths that disagree with the row offsets must not write past the table
+            for (int k = 0; k < v && first + k < max_items; ++k) item_seq[first + k] = i;
+        }
+        __syncthreads();
+        if (threadIdx.x == 255) *carry = c + buf[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tile_start[n_seq] = *carry;
+}
 
 // ----------------------------------------------------------------------------- attention
 // Both take the same (n_seq, n_tokens, max_pages): the blocking they derive from them must agree.

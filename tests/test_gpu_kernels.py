@@ -111,6 +111,11 @@ def run_attention(ctx, cfg, c, prefix_len):
     ("hd128_key_split", lambda: inputs.qwen32b_cfg(1), [16, 8, 33], [4100, 1500, 20]),
     # 73 key tiles in 9 splits: the last split is one diagonal tile in which the first 30 tokens see no key
     ("tiny_key_split_rows_without_keys", inputs.tiny_cfg, [64], [4578]),
+    # more than 128 query rows per sequence (two or three row blocks walk the same split key range): an odd and an
+    # even number of tiles per split, a last row block with few rows, a sequence too short to split
+    ("hd128_wide_key_split", lambda: inputs.qwen32b_cfg(1), [40, 64, 30, 52], [4100, 1500, 700, 90]),
+    ("tiny_wide_key_split", inputs.tiny_cfg, [150, 100, 129], [3000, 2047, 5]),
+    ("hd128_wide_key_split_one_request", lambda: inputs.qwen32b_cfg(1), [64], [4032]),
 ])
 def test_attention_matches_oracle(name, cfgf, new_len, prefix_len):
     cfg = cfgf()
