@@ -279,6 +279,9 @@ def test_config4_long_prefill_in_chunks(model):
     i0 = int(np.argmin(case.new_len))
     _, _, floor = assert_parity(f"config4 shortest prompt ({case.new_len[i0]} tokens, chunked)",
                                 y[case.cu[i0]:case.cu[i0 + 1]], case, [i0])
+    # appended K/V of the shortest prompt (1090 rows: the 256-row projection tiles, one K slice, then RoPE + append)
+    _, ks, vs, _ = case.oracle(seqs=[i0])
+    assert_new_kv("config4", case, 0, [i0], ks[0], vs[0])
     i1 = int(np.argsort(case.new_len)[1])
     assert case.new_len[i1] > 2048
     assert_parity(f"config4 second shortest prompt ({case.new_len[i1]} tokens in 2 chunks) vs the unchunked oracle",
