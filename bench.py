@@ -4,10 +4,11 @@
 Primary workload (the short-prefill bucket configuration, configs[1] of the benchmark definition): 256 new
 prompts, lengths U[8,64], bucketed to {16,32,64}, 4-layer stack of 32B-shaped layers, every bucket batch replayed
 as a captured hipGraph.  One "step" = plan + stage + replay of every batch of the 256 requests.
-Also reported in the same JSON line: the same workload at larger token budgets (`short_budget_sweep`,
-`short_token_max`) and on two streams, the multi-turn re-prefill workload (`reprefill`), the long-prefill workload
-(`long_prefill`), the latency-model fit, the graph cost table, the simulated instance pools, the mixed dual-queue
-workload (`dual_queue`), and the fp64 oracle timed on the host cores (`cpu_baseline`).
+The last line on stdout is one compact JSON record: the headline, the roofline of the dominant kernel, the other
+workloads' key figures (token-max budgets, two streams, the multi-turn re-prefill workload, the long-prefill workload,
+the latency-model fit with the schedule parameters derived from it, the mixed dual-queue workload) and the fp64 oracle
+timed on the host cores (`cpu_baseline`).  The full record of every leg, including the budget sweep, the graph cost
+table and the simulated instance pools, goes to `gpurun_out/<--detail-file>`.
 """
 from __future__ import annotations
 
@@ -41,14 +42,13 @@ def pct(v, q):
 
 
 def source_digest():
-    """sha256 over the kernel sources: measured counter figures under profiles/ are stamped with it."""
+    """sha256 over the GEMM kernel sources: the counter figures under profiles/traffic.json are stamped with it."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2601_11589_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h")):
-            with open(os.path.join(csrc, name), "rb") as f:
-                h.update(name.encode() + b"\0" + f.read())
+    for name in ("gemm.hip", "laps_internal.h"):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()
 
 
