@@ -25,6 +25,8 @@
 // the splits a given sequence really uses is decided on the device from its length.
 #include "laps_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int KT = 64;      // keys per tile (4 pages)
@@ -144,57 +146,48 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
         for (int i = 0; i < 16; ++i) o[ni][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;   // running max (in log2 units, already scaled) and partial row sum
 
-    // ---- tile copy assignment: chunk c = tid + i*NTHR of the tile's 4 pages
-    // The page ids of a tile are fetched one step before its data, so that the two dependent loads (table entry,
-    // then the page itself) do not add up on the critical path of every tile.
-    u32x4 kreg[NLD], vreg[NLD];
-    int pgn[NLD];
-    auto load_pages = [&](int j0) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            int pidx = j0 / LAPS_PAGE + (tid + i * NTHR) / CPP;
-            pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
-            pgn[i] = pt[pidx];
-        }
+    // ---- tile copy assignment: chunk c = tid + i*NTHR of the tile's 4 pages.  All chunks a wave copies in one
+    // pass lie in one page, so the page id is a wave-uniform (scalar) load.
+    u32x4 kreg[NLD], vreg[NLD];   // landing registers of the tile copy
+    auto page_id = [&](int j0, int i) -> int {
+        int pidx = j0 / LAPS_PAGE + __builtin_amdgcn_readfirstlane((tid + i * NTHR) / CPP);
+        pidx = pidx < n_pages_seq ? pidx : n_pages_seq - 1;  // past the end: any valid page, masked later
+        return pt[pidx];
     };
-    auto load_tile = [&](int j0) {   // uses the ids load_pages(j0) fetched
+    auto chunk_offset = [&](int pg, int i) -> size_t {
+        const int within = (tid + i * NTHR) % CPP;
+        // an unset (-1) entry or an id outside the pool must not turn into a wild address
+        const size_t page = (size_t)((pg > 0 && pg < n_pool_pages) ? pg : 0);
+        return (page * n_kv + kvh) * CPP + within;
+    };
+    auto store_k = [&](int buf) {   // K page is [16 keys][HD]
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int c = tid + i * NTHR;
-            const int within = c % CPP;
-            const int pg = pgn[i];
-            // an unset (-1) entry or an id outside the pool must not turn into a wild address
-            const size_t page = (size_t)((pg > 0 && pg < n_pool_pages) ? pg : 0);
-            const size_t off = ((page * n_kv + kvh) * CPP + within);
-            kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
-            vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];
+            const int pi = c / CPP, within = c % CPP;
+            const int key = pi * LAPS_PAGE + within / CPR, kc = within % CPR;
+            Ks[buf][key * CPR + (CPR == 16 ? swz16(key, kc) : swz8(key, kc))] = kreg[i];
         }
     };
-    auto store_tile = [&](int j0, int buf) {
+    auto store_v = [&](int j0, int buf) {   // V page is [HD][16 keys]: chunk = 8 consecutive keys of one head_dim index
         const bool tail = (j0 + KT > kv_len);
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int c = tid + i * NTHR;
             const int pi = c / CPP, within = c % CPP;
-            {   // K page is [16 keys][HD]
-                const int key = pi * LAPS_PAGE + within / CPR, kc = within % CPR;
-                Ks[buf][key * CPR + (CPR == 16 ? swz16(key, kc) : swz8(key, kc))] = kreg[i];
-            }
-            {   // V page is [HD][16 keys]: chunk = 8 consecutive keys of one head_dim index
-                const int e = within / 2, half = within & 1;
-                u32x4 v = vreg[i];
-                if (tail) {  // zero keys >= kv_len so that 0 * garbage cannot produce NaN
-                    const int nvalid = kv_len - (j0 + pi * LAPS_PAGE + half * 8);
+            const int e = within / 2, half = within & 1;
+            u32x4 v = vreg[i];
+            if (tail) {  // zero keys >= kv_len so that 0 * garbage cannot produce NaN
+                const int nvalid = kv_len - (j0 + pi * LAPS_PAGE + half * 8);
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        unsigned x = v[w];
-                        if (2 * w + 1 >= nvalid) x &= 0x0000ffffu;
-                        if (2 * w >= nvalid) x = 0u;
-                        v[w] = x;
-                    }
+                for (int w = 0; w < 4; ++w) {
+                    unsigned x = v[w];
+                    if (2 * w + 1 >= nvalid) x &= 0x0000ffffu;
+                    if (2 * w >= nvalid) x = 0u;
+                    v[w] = x;
                 }
-                Vs[buf][e * 8 + swz8(e, pi * 2 + half)] = v;
             }
+            Vs[buf][e * 8 + swz8(e, pi * 2 + half)] = v;
         }
     };
 
@@ -202,63 +195,188 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
     const int ra = lm >> 3, rh = (lm >> 2) & 1, rb = lm & 3;
     const int krow = 16 * (ra >> 1) + 8 * rh + 4 * (ra & 1) + rb;
 
-    auto compute_tile = [&](int j0, int buf) {
-        if (j0 <= vis_max) {  // wave-uniform: something of this tile is visible to this wave
-            // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key sub-tiles)
-            f32x16 s[2];
+    // operand fragments: K for matrix instruction g = 2 kk + sub of the first product, V^T for g = NI u2 + ni of
+    // the second
+    auto k_frag = [&](int kb, int g) -> bf16x8 {
+        const int row = (g & 1) * 32 + krow, ch = (g >> 1) * 2 + lh;
+        return __builtin_bit_cast(bf16x8, Ks[kb][row * CPR + (CPR == 16 ? swz16(row, ch) : swz8(row, ch))]);
+    };
+    auto v_frag = [&](int vb, int g) -> bf16x8 {
+        const int row = (g % NI) * 32 + lm;
+        return __builtin_bit_cast(bf16x8, Vs[vb][row * 8 + swz8(row, (g / NI) * 2 + lh)]);
+    };
+    // S^T = K Q^T for the 64 keys of the tile in Ks[kb] (two 32-key sub-tiles)
+    auto qk_tile = [&](int kb, f32x16 (&s)[2]) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) {
+        for (int g = 0; g < 2 * KSTEPS; ++g)
+            s[g & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(kb, g), qf[g >> 1], s[g & 1], 0, 0, 0);
+    };
+    // causal mask, needed on diagonal tiles only (wave-uniform test by the caller)
+    auto mask_tile = [&](int j0, f32x16 (&s)[2]) {
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) {
-                    const int row = sub * 32 + krow;
-                    const int ch = kk * 2 + lh;
-                    const bf16x8 kf = __builtin_bit_cast(
-                        bf16x8, Ks[buf][row * CPR + (CPR == 16 ? swz16(row, ch) : swz8(row, ch))]);
-                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int a = i >> 2, b = i & 3;
+                const int key = j0 + sub * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
+                s[sub][i] = (key <= limit) ? s[sub][i] : -INFINITY;
+            }
+    };
+    // online softmax of one tile's scores, one query row per lane (shared with lane^32): probabilities as the
+    // second product's operand, the tile's row maximum and row sum; softmax_finish folds them into the running
+    // state and rescales O when some row's maximum moved
+    // The reference value m_run that the exponentials subtract follows the row maximum lazily: it moves (and O and
+    // the row sum are rescaled) only when some row's maximum has grown by more than RESCALE_SLACK in log2 units, so
+    // probabilities stay below 2^RESCALE_SLACK and the 64-register rescale of O is rare.  The quotient O / l does
+    // not depend on the reference.
+    constexpr float RESCALE_SLACK = 8.f;
+    const int partner_addr = (lane ^ 32) << 2;   // ds_bpermute address of the lane that shares this lane's row
+    auto from_partner = [&](float x) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(partner_addr, __builtin_bit_cast(int, x)));
+    };
+    float m_new, psum;
+    bool moved;   // wave-uniform: the reference moves to m_new after this tile
+    auto pick_reference = [&](float mx) -> float {   // returns what this tile's exponentials subtract
+        m_new = fmaxf(m_run, mx * scale_log2e);
+        moved = __builtin_amdgcn_ballot_w64(m_new > m_run + RESCALE_SLACK) != 0;
+        const float m_use = moved ? m_new : m_run;
+        // un-split: finite from the first tile on (key 0 is visible to every row).  A later split can start
+        // on a diagonal tile in which a row sees nothing yet: keep exp2(-inf - -inf) out of the arithmetic.
+        return (SPLIT && m_use == -INFINITY) ? 0.f : m_use;
+    };
+    auto softmax_tile = [&](f32x16 (&s)[2], bf16x8 (&pf)[2][2]) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[sub][i]);
+        mx = fmaxf(mx, from_partner(mx));
+        const float m_sub = pick_reference(mx);
+        psum = 0.f;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 pk;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + e], scale_log2e, -m_sub));
+                    psum += p;
+                    pk[e] = (__bf16)p;
                 }
+                pf[sub][u] = pk;
             }
-            // ---- causal mask (diagonal tiles only) + online softmax, one query row per lane (shared with lane^32)
-            if (j0 + KT - 1 > vis_min) {
+    };
+    auto softmax_finish = [&]() {
+        if (moved) {
+            const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= alpha;
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int a = i >> 2, b = i & 3;
-                        const int key = j0 + sub * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
-                        s[sub][i] = (key <= limit) ? s[sub][i] : -INFINITY;
-                    }
+                for (int i = 0; i < 16; ++i) o[ni][i] *= alpha;
+            m_run = m_new;
+        }
+        l_run += psum;
+    };
+    // O^T += V^T P^T with the tile in Vs[vb]
+    auto pv_tile = [&](int vb, bf16x8 (&pf)[2][2]) {
+#pragma unroll
+        for (int g = 0; g < 4 * NI; ++g)
+            o[g % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(vb, g), pf[g / (2 * NI)][(g / NI) & 1], o[g % NI], 0, 0, 0);
+    };
+
+    const auto exists = [&](int j) { return j < kv_end; };
+    if constexpr (NW == 8) {
+        // Long prompts.  The loop is software-pipelined three deep over 32-key half tiles: in step w the matrix
+        // cores form the scores of half tile w + 1 and add half tile w - 1 to O while the vector ALU turns the scores
+        // of half tile w into probabilities - one matrix instruction, one LDS fragment read and a share of the
+        // softmax per slot, so both pipes are busy in every wave whatever phase the other wave of its SIMD is in.
+        // Tile t occupies Ks[t&1] and Vs[t&1].  Tile step t runs the half steps 2t and 2t + 1:
+        //   2t    : scores of (t, keys 32..63), softmax of (t, keys 0..31), O += (t-1, keys 32..63)
+        //   barrier: K(t) and V(t-1) are done with; K(t+2) and V(t+1) leave the registers for their buffers
+        //   2t + 1: scores of (t+1, keys 0..31), softmax of (t, keys 32..63), O += (t, keys 0..31)
+        // and there is one tile step more than tiles (its first half adds the last half tile to O).
+        // page ids (scalars) are fetched one tile step before the loads that use them
+        int idk[NLD], idv[NLD];
+        auto fetch_ids = [&](int jk, int jv) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) idk[i] = page_id(jk, i), idv[i] = page_id(jv, i);
+        };
+        auto load_k = [&]() {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[chunk_offset(idk[i], i)];
+        };
+        auto load_v = [&]() {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[chunk_offset(idv[i], i)];
+        };
+        // wave-uniform: half tile (tile at key j, half h) exists and some row of this wave sees one of its keys
+        const auto visible = [&](int j, int h) { return j >= kv_begin && j < kv_end && j + 32 * h <= vis_max; };
+        constexpr int NQ = KSTEPS;       // matrix instructions of each product per half tile (equal: HD / 16)
+        constexpr int NS = 2 * NQ;       // slots per half step
+        constexpr int MAXS = NS >= 16 ? NS / 8 : 1;   // slots that take the row maximum
+        constexpr int EXP0 = MAXS + 2;   // first slot of the exponentials
+        constexpr int NE = NS + 2 - EXP0;   // slots that share the 16 exponentials
+        static_assert(2 * NI == NQ, "both products issue HD / 16 matrix instructions per half tile");
+        // the three stages one after the other, for the first and last half steps of a wave
+        auto qk_half = [&](int kb, int h, f32x16& sc) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk)
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(kb, 2 * kk + h), qf[kk], sc, 0, 0, 0);
+        };
+        auto mask_half = [&](int j0, int h, f32x16& sc) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int a = i >> 2, b = i & 3;
+                const int key = j0 + h * 32 + 16 * (a >> 1) + 8 * lh + 4 * (a & 1) + b;
+                sc[i] = (key <= limit) ? sc[i] : -INFINITY;
             }
+        };
+        // Row sums come from the matrix cores as well: a fragment of ones times P^T gives, in every register of the
+        // result, the sum over the fragment's keys of the probabilities as the second product sees them (rounded to
+        // bf16), complete in both lanes of a row.  It is added to l_run where the same probabilities are added to O.
+        bf16x8 ones;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+        auto softmax_half = [&](f32x16& sc, bf16x8 (&pf)[2]) {
             float mx = -INFINITY;
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[i]);
+            mx = fmaxf(mx, from_partner(mx));
+            const float m_sub = pick_reference(mx);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[sub][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            // un-split: finite from the first tile on (key 0 is visible to every row).  A later split can start
-            // on a diagonal tile in which a row sees nothing yet: keep exp2(-inf - -inf) out of the arithmetic.
-            const float m_new = fmaxf(m_run, mx * scale_log2e);
-            const float m_sub = (SPLIT && m_new == -INFINITY) ? 0.f : m_new;
-            bf16x8 pf[2][2];
-            float psum = 0.f;
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 pk;
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+                for (int e = 0; e < 8; ++e)
+                    pk[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sc[8 * u + e], scale_log2e, -m_sub));
+                pf[u] = pk;
+            }
+        };
+        auto pv_half = [&](int vb, int h, bf16x8 (&pf)[2]) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    bf16x8 pk;
+            for (int g = 0; g < 2 * NI; ++g)
+                o[g % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(vb, (2 * h + g / NI) * NI + g % NI), pf[g / NI],
+                                                                    o[g % NI], 0, 0, 0);
+            f32x16 ls;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + e], scale_log2e, -m_sub));
-                        psum += p;
-                        pk[e] = (__bf16)p;
-                    }
-                    pf[sub][u] = pk;
-                }
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row's maximum moved: rescale
-                const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+            for (int i = 0; i < 16; ++i) ls[i] = 0.f;
+            ls = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[0], ls, 0, 0, 0);
+            ls = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[1], ls, 0, 0, 0);
+            l_run += ls[0];
+        };
+        // moves the reference to m_new after the matrix work of a half step (the probabilities just formed already
+        // use it; O and l_run, which hold the half tiles before, follow here)
+        auto move_reference = [&]() {
+            if (moved) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 l_run *= alpha;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
@@ -266,46 +384,166 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_kernel(const bf16_t* __restri
                     for (int i = 0; i < 16; ++i) o[ni][i] *= alpha;
                 m_run = m_new;
             }
-            l_run += psum;
-            // ---- O^T += V^T P^T
+        };
+        // one half step.  (kb, hq): buffer and half of the scores to form into s_nxt; s_cur -> pf_cur; (vb, hv):
+        // buffer and half of the V tile that goes with pf_prev
+        auto half_step = [&](bool do_qk, bool do_sm, bool do_pv, int kb, int hq, f32x16& s_nxt, f32x16& s_cur,
+                             bf16x8 (&pf_cur)[2], int vb, int hv, bf16x8 (&pf_prev)[2]) __attribute__((always_inline)) {
+            if (do_qk && do_sm && do_pv) {
+                // slot g < NS: even = first product's instruction g / 2, odd = second product's; the last two slots
+                // take the row sums.  The LDS fragment of slot g + 2 is read in slot g.
+                bf16x8 fr[NS + 2];
+                fr[0] = k_frag(kb, hq);
+                fr[1] = v_frag(vb, 2 * hv * NI);
+                f32x16 ls;
 #pragma unroll
-            for (int u2 = 0; u2 < 4; ++u2) {
+                for (int i = 0; i < 16; ++i) s_nxt[i] = 0.f, ls[i] = 0.f;
+                float cmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                float mx = 0.f, mx_other = 0.f, m_sub = 0.f;
+                bf16x8 pk;
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int row = ni * 32 + lm;
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, Vs[buf][row * 8 + swz8(row, u2 * 2 + lh)]);
-                    o[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u2 >> 1][u2 & 1], o[ni], 0, 0, 0);
+                for (int g = 0; g < NS + 2; ++g) {
+                    const int q = g >> 1;   // index within its product
+                    if (g >= NS)
+                        ls = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf_prev[g - NS], ls, 0, 0, 0);
+                    else if (g & 1)
+                        o[q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], pf_prev[q / NI], o[q % NI], 0, 0, 0);
+                    else
+                        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g], qf[q], s_nxt, 0, 0, 0);
+                    if (g + 2 < NS) {
+                        const int q2 = (g + 2) >> 1;
+                        fr[g + 2] = ((g + 2) & 1) ? v_frag(vb, (2 * hv + q2 / NI) * NI + q2 % NI) : k_frag(kb, 2 * q2 + hq);
+                    }
+                    // ---- this slot's share of the softmax
+                    if (g < MAXS) {   // four independent chains over 16 / MAXS values per slot
+                        constexpr int PER = 16 / MAXS;
+#pragma unroll
+                        for (int k = 0; k < PER; ++k) cmax[k & 3] = fmaxf(cmax[k & 3], s_cur[g * PER + k]);
+                    } else if (g == MAXS) {
+                        mx = fmaxf(fmaxf(cmax[0], cmax[1]), fmaxf(cmax[2], cmax[3]));
+                        mx_other = from_partner(mx);
+                    } else if (g == MAXS + 1) {
+                        m_sub = pick_reference(fmaxf(mx, mx_other));
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) {
+                            if ((k * NE) / 16 != g - EXP0) continue;
+                            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[k], scale_log2e, -m_sub));
+                            asm volatile("" : "+v"(p));   // keeps the exponential in its slot (it would sink below
+                                                          // the rescale branch, out from under the matrix work)
+                            pk[k & 7] = (__bf16)p;
+                            if ((k & 7) == 7) pf_cur[k >> 3] = pk;
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                l_run += ls[0];
+                move_reference();
+            } else {
+                if (do_qk) qk_half(kb, hq, s_nxt);
+                if (do_sm) softmax_half(s_cur, pf_cur);
+                if (do_pv) pv_half(vb, hv, pf_prev);
+                if (do_sm) move_reference();
+            }
+        };
+        f32x16 s_lo, s_hi;            // scores of keys 0..31 / 32..63 of a tile
+        bf16x8 p_lo[2], p_hi[2];      // their probabilities
+        auto tile_step = [&](int j0, auto parity) __attribute__((always_inline)) {
+            constexpr int b = decltype(parity)::value;   // j0's tile sits in buffers b, its neighbours in b ^ 1
+            {
+                const bool sm = visible(j0, 0);
+                if (sm && j0 + 31 > vis_min) mask_half(j0, 0, s_lo);
+                half_step(visible(j0, 1), sm, visible(j0 - KT, 1), b, 1, s_hi, s_lo, p_lo, b ^ 1, 1, p_hi);
+            }
+            __syncthreads();
+            if (exists(j0 + 2 * KT)) store_k(b);
+            if (exists(j0 + KT)) store_v(j0 + KT, b ^ 1);
+            if (exists(j0 + 3 * KT)) load_k();
+            if (exists(j0 + 2 * KT)) load_v();
+            fetch_ids(j0 + 4 * KT, j0 + 3 * KT);   // clamped to the sequence's pages: harmless past the end
+            {
+                const bool sm = visible(j0, 1);
+                if (sm && j0 + 63 > vis_min) mask_half(j0, 1, s_hi);
+                half_step(visible(j0 + KT, 0), sm, visible(j0, 0), b ^ 1, 0, s_lo, s_hi, p_hi, b, 0, p_lo);
+            }
+        };
+        // SPLIT is never combined with this variant: a wave's first half tile always shows key 0 to every row, so
+        // the running maximum is finite from the first softmax on
+        static_assert(!SPLIT, "the pipelined loop serves un-split launches only");
+        fetch_ids(kv_begin, kv_begin);
+        load_k();
+        load_v();
+        fetch_ids(kv_begin + KT, kv_begin + KT);
+        store_k(0);
+        store_v(kv_begin, 0);
+        if (exists(kv_begin + KT)) load_k();
+        fetch_ids(kv_begin + 2 * KT, kv_begin + KT);
+        __syncthreads();
+        if (visible(kv_begin, 0)) qk_half(0, 0, s_lo);
+        if (exists(kv_begin + KT)) store_k(1);
+        if (exists(kv_begin + 2 * KT)) load_k();
+        if (exists(kv_begin + KT)) load_v();
+        fetch_ids(kv_begin + 3 * KT, kv_begin + 2 * KT);
+        for (int j0 = kv_begin; j0 < kv_end + KT; j0 += 2 * KT) {   // two tile steps: the buffers swap roles
+            tile_step(j0, std::integral_constant<int, 0>{});
+            if (j0 + KT < kv_end + KT) tile_step(j0 + KT, std::integral_constant<int, 1>{});
+        }
+    } else {
+        // Short prompts and key-range splits: a few tiles per workgroup, latency matters more than overlap.  The
+        // page ids of a tile are fetched one step before its data, so that the two dependent loads (table entry,
+        // then the page itself) do not add up on the critical path of every tile.
+        int pgn[NLD];
+        auto load_pages = [&](int j0) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) pgn[i] = page_id(j0, i);
+        };
+        auto load_tile = [&]() {   // uses the ids load_pages fetched
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const size_t off = chunk_offset(pgn[i], i);
+                kreg[i] = reinterpret_cast<const u32x4*>(k_pool)[off];
+                vreg[i] = reinterpret_cast<const u32x4*>(v_pool)[off];
+            }
+        };
+        load_pages(kv_begin);
+        load_tile();
+        load_pages(kv_begin + KT);        // indices are clamped to the sequence's pages: harmless past the end
+        store_k(0);
+        store_v(kv_begin, 0);
+        if (exists(kv_begin + KT)) {
+            load_tile();
+            load_pages(kv_begin + 2 * KT);
+        }
+        __syncthreads();
+        int buf = 0;
+        for (int j0 = kv_begin; j0 < kv_end; j0 += KT, buf ^= 1) {
+            // stage the next tile (already in registers) into the other buffer, refill the registers
+            if (exists(j0 + KT)) {
+                store_k(buf ^ 1);
+                store_v(j0 + KT, buf ^ 1);
+                if (exists(j0 + 2 * KT)) {
+                    load_tile();
+                    load_pages(j0 + 3 * KT);
                 }
             }
-        }
-    };
-    load_pages(kv_begin);
-    load_tile(kv_begin);
-    load_pages(kv_begin + KT);        // indices are clamped to the sequence's pages: harmless past the end
-    store_tile(kv_begin, 0);
-    if (kv_begin + KT < kv_end) {
-        load_tile(kv_begin + KT);
-        load_pages(kv_begin + 2 * KT);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int j0 = kv_begin; j0 < kv_end; j0 += KT, buf ^= 1) {
-        // stage the next tile (already in registers) into the other buffer, refill the registers.  (A second
-        // register set, two tiles in flight, spills at head_dim 128: the landing registers are the limit.)
-        if (j0 + KT < kv_end) {
-            store_tile(j0 + KT, buf ^ 1);
-            if (j0 + 2 * KT < kv_end) {
-                load_tile(j0 + 2 * KT);
-                load_pages(j0 + 3 * KT);
+            if (j0 <= vis_max) {  // wave-uniform: something of this tile is visible to this wave
+                f32x16 sc[2];
+                bf16x8 pf[2][2];
+                qk_tile(buf, sc);
+                if (j0 + KT - 1 > vis_min) mask_tile(j0, sc);
+                softmax_tile(sc, pf);
+                softmax_finish();
+                pv_tile(buf, pf);
             }
+            __syncthreads();
         }
-        compute_tile(j0, buf);
-        __syncthreads();
     }
 
     // ---- normalise and store: lane owns row r; register i of sub-tile ni is head_dim index
     //      ni*32 + 8*(i/4) + 4*(lane/32) + i%4
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    // the pipelined loop holds complete row sums, the plain one a lane's share
+    const float l_tot = (NW == 8) ? l_run : l_run + __shfl_xor(l_run, 32, 64);
     if (SPLIT && eff > 1) {
         // partial result of this key range: accumulator as [4-float chunk][row] so that the 32 rows of a half
         // wave write consecutive 16-byte pieces; (running max, row sum) per row
