@@ -548,7 +548,7 @@ def main():
     ap.add_argument("--no-latency-model", action="store_true", help="skip the run-time latency-model fit")
     ap.add_argument("--no-reprefill", action="store_true", help="skip the multi-turn re-prefill workload (configs[2])")
     ap.add_argument("--no-graph-cost", action="store_true", help="skip the graph capture cost table (7B/14B/32B shapes)")
-    ap.add_argument("--windows-us", type=str, default="0,2000,10000", help="waiting windows for the dual-queue sweep")
+    ap.add_argument("--windows-us", type=str, default="0,500,1000,2000,10000", help="waiting windows (us) for the dual-queue sweep")
     ap.add_argument("--budget-sweep", type=str, default="256,512,1024",
                     help="further token budgets for the short workload (tokens/s against latency); empty = none")
     ap.add_argument("--no-two-streams", action="store_true",

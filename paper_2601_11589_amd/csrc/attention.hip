@@ -16,6 +16,12 @@
 // lane holds in accumulator registers 8u..8u+7 exactly the eight consecutive keys its P fragment
 // must supply to the second product - no shuffles between the two MFMA stages.
 //
+// Two loops share these pieces.  Workgroups of 4 waves (short prompts, split key ranges) take a tile at a time:
+// scores, softmax, second product, one barrier.  Workgroups of 8 waves (long prompts) run a three-stage software
+// pipeline over 32-key half tiles, in which the matrix cores work on the half tiles before and after the one whose
+// softmax the vector ALU is computing; its row sums also come from the matrix cores.  In both, the value the
+// exponentials subtract follows the row maximum lazily, so that O is rescaled rarely.
+//
 // Few query rows over a long cached prefix (a short re-prefill turn) would leave most of the chip idle:
 // one request of 16 new tokens is a single row block per kv head.  For such launches the key range is
 // split over gridDim.z workgroups (at least 4 key tiles each); every split writes its un-normalised
