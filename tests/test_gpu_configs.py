@@ -296,34 +296,31 @@ def test_config4_long_prefill_in_chunks(model):
     assert rel < 2.0 * floor, (rel, floor)
 
 
-def test_config4_longest_prompt_in_four_chunks_through_one_layer(model):
-    """The longest prompt of the configuration (7991 tokens) in four chunks through the first layer, against the
-    unchunked oracle: the last chunk's 1847 rows attend to 6144 keys that the three chunks before it appended, in the
-    launch shapes of the long-prefill workload.  One layer keeps the fp64 side to about a minute; the depth of the
-    stack is covered by the shorter prompts above."""
-    _, _, host_layers, dev_layers = model
+def test_config4_longest_prompt_in_four_chunks_through_the_stack(model):
+    """The longest prompt of the configuration (7991 tokens) in four chunks through all four layers, against the
+    unchunked oracle: the last chunk's 1847 rows attend to 6144 keys that the three chunks before it appended, at
+    every layer, in the launch shapes of the long-prefill workload.  The fp64 side (the pure oracle and the one with
+    the bf16 storage points) takes a few minutes of host time; it is the only check of this depth at this length."""
+    cfg, ctx, host_layers, dev_layers = model
     b = inputs.make_batch(4)
     i = int(np.argmax(b.new_len))
     n = int(b.new_len[i])
     assert n > 3 * 2048
-    cfg1 = inputs.qwen32b_cfg(1)
-    ctx1 = api.LapsCtx(cfg1, max_positions=8192 + 64)
-    case = SharedCase(cfg1, [n], [0], inputs.SEED_BASE + 4, host_layers[:1], dev_layers[:1]).to_device(ctx1)
+    case = SharedCase(cfg, [n], [0], inputs.SEED_BASE + 4, host_layers, dev_layers).to_device(ctx)
     plan = api.laps_plan_buckets(64, LEN_BUCKETS, DEPTHS, 128, 2048, case.new_len, case.prefix_len)
     chunks = plan["longs"][0]["chunks"]
     assert len(chunks) == 4 and sum(chunks) == n
     stream = torch.cuda.Stream()
     out = torch.empty_like(case.d_x)
-    ctx1.workspace(2048, 1)
-    keep = runner.run_long_chunks(ctx1, dev_layers[:1], case.k_pools, case.v_pools, case.d_x, 0, case.d_page_table[0:1],
+    ctx.workspace(2048, 1)
+    keep = runner.run_long_chunks(ctx, dev_layers, case.k_pools, case.v_pools, case.d_x, 0, case.d_page_table[0:1],
                                   chunks, stream, out)
     stream.synchronize()
     cache = {}
-    assert_parity(f"config4 longest prompt ({n} tokens in 4 chunks, first layer) vs the unchunked oracle",
+    assert_parity(f"config4 longest prompt ({n} tokens in 4 chunks, {cfg.n_layers} layers) vs the unchunked oracle",
                   out.cpu().numpy(), case, [0], cache)
     assert_new_kv("config4 longest prompt", case, 0, [0], cache["ks"][0], cache["vs"][0])
     del keep
-    ctx1.close()
 
 
 @pytest.mark.parametrize("name,cfgf", [("7B", inputs.qwen7b_cfg), ("14B", inputs.qwen14b_cfg)])
