@@ -364,8 +364,8 @@ class Config5State:
 @pytest.fixture(scope="module")
 def config5(model8):
     """configs[4] resident in HBM: 4 long prompts + 512 short / re-prefill requests on the 8-layer stack, with
-    four sampled requests (3 short + the shortest long) whose prefix KV is seeded from the host so that the
-    oracle can follow them."""
+    nine sampled requests (2 fresh short prompts, 6 re-prefills from the shortest to the longest cached prefix, and
+    the shortest long prompt) whose prefix KV is seeded from the host so that the oracle can follow them."""
     from paper_2601_11589_amd import dualqueue
     cfg, ctx, host_layers, dev_layers = model8
     st = Config5State()
@@ -379,10 +379,11 @@ def config5(model8):
         p.copy_(torch.randn(p.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
     is_long = b.new_len > 64
     shorts = np.nonzero(~is_long)[0]
-    fresh = int(next(i for i in shorts if b.prefix_len[i] == 0))
-    with_pre = [int(i) for i in shorts if b.prefix_len[i] > 0]
-    sample = [fresh, min(with_pre, key=lambda i: b.prefix_len[i]), with_pre[len(with_pre) // 2],
-              int(min(np.nonzero(is_long)[0], key=lambda i: b.new_len[i]))]
+    fresh = [int(i) for i in shorts if b.prefix_len[i] == 0][:2]
+    with_pre = sorted((int(i) for i in shorts if b.prefix_len[i] > 0), key=lambda i: int(b.prefix_len[i]))
+    spread = [with_pre[int(q * (len(with_pre) - 1))] for q in (0.0, 0.2, 0.4, 0.6, 0.8, 1.0)]   # shortest .. longest prefix
+    sample = fresh + spread + [int(min(np.nonzero(is_long)[0], key=lambda i: b.new_len[i]))]
+    assert len(set(sample)) == len(sample) == 9
     # the sampled requests get seeded host-side prefix KV, written into their pages of the big pools
     sub = SharedCase(cfg, b.new_len[sample], b.prefix_len[sample], seed, host_layers, dev_layers)
     cu_all = b.cu_seqlens
@@ -409,7 +410,7 @@ def test_config5_dual_queue_step_loop(config5):
     st, dq, b, is_long = config5, config5.dq, config5.b, config5.is_long
     zeros = np.zeros(b.n)
     rd = dq.run_disaggregated(zeros, window_us=0.0)
-    assert_parity("config5 disaggregated (3 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
+    assert_parity("config5 disaggregated (8 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
     dq.out.zero_()
     ru = dq.run_unified(zeros)
     assert_parity("config5 unified mixed batches (same requests)", st.sampled_rows(), st.sub, None, st.cache)
@@ -434,7 +435,7 @@ def test_config5_awd_policy(config5):
     st, dq, b, is_long = config5, config5.dq, config5.b, config5.is_long
     dq.out.zero_()
     ra = dq.run_awd(np.zeros(b.n))
-    assert_parity("config5 AWD deadline-free (3 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
+    assert_parity("config5 AWD deadline-free (8 short + shortest long)", st.sampled_rows(), st.sub, None, st.cache)
     assert np.all(ra.finish_us > 0)
     assert ra.step_kinds["long_chunk"] == int(sum(-(-int(l) // 2048) for l in b.new_len[is_long]))
     assert ra.step_kinds["dispatch_reasons"].get("depth", 0) >= 1          # all waiting at t=0: rounds fill D at once
