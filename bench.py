@@ -27,6 +27,7 @@ MFMA_BF16_PEAK_TFS = 2500.0
 LEN_BUCKETS = [16, 32, 64]
 DEPTHS = [1, 2, 4, 8, 16, 32, 64]
 LONG_CHUNK = 2048
+WHOLE_PROMPT_BUDGET = 16384   # tokens per step of the un-chunked memory-based baseline: the longest prompt (8K) and more
 
 
 _T0 = time.perf_counter()
@@ -462,6 +463,7 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,), params=None):
     log("[bench:dual-queue] warm-up and back-to-back passes")
     dq.run_disaggregated(zeros, 0.0)          # warm-up: captures every bucket shape the workload needs
     dq.run_unified(zeros)
+    dq.run_unified(zeros, budget=WHOLE_PROMPT_BUDGET)
     u0 = dq.run_unified(zeros)
     d0 = dq.run_disaggregated(zeros, 0.0)
     # algorithmic flops of the whole workload: projections on real tokens + causal attention over prefix and new tokens
@@ -476,7 +478,8 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,), params=None):
 
     res = {"requests": int(b.n), "real_tokens": int(b.n_tokens), "layers": cfg8.n_layers,
            "algorithmic_TFLOP": total_flops / 1e12,
-           "back_to_back": {"unified": summ(u0), "disaggregated": summ(d0)}, "poisson": []}
+           "back_to_back": {"unified": summ(u0), "unified_whole_prompts": summ(dq.run_unified(zeros, budget=WHOLE_PROMPT_BUDGET)),
+                            "disaggregated": summ(d0)}, "poisson": []}
     s_hat = d0.step_kinds["short_busy_us"] / max(d0.step_kinds["short_graph"], 1)   # mean short step, measured
     dq.run_awd(zeros)                          # warm-up: captures the fused shapes AWD dispatches
     res["back_to_back"]["awd"] = summ(dq.run_awd(zeros, s_hat_us=s_hat))
@@ -490,6 +493,8 @@ def run_dual_queue(ctx8, layers8, cfg8, windows_us, loads=(0.7,), params=None):
             arr[i] = horizon * j / len(longs)
         tag = {"load": ld, "arrival_rate_per_s": rate}
         res["poisson"].append(summ(dq.run_unified(arr), tag))
+        # memory-based batching without chunks (Section 2.3): a long prompt enters whole, short requests ride behind it
+        res["poisson"].append(summ(dq.run_unified(arr, budget=WHOLE_PROMPT_BUDGET), tag))
         for w in (windows_us if ld == loads[len(loads) // 2] else windows_us[1:2]):   # full window sweep at the middle load
             res["poisson"].append(summ(dq.run_disaggregated(arr, float(w)), tag))
         # Adaptive-Wait-Depth batching of the short queue (Algorithm 1): deadline-free, then with a 50 ms TTFT deadline

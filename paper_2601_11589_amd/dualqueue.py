@@ -12,7 +12,9 @@ paper's "graph fusion", Section 3.1): a replay then costs one pass over the weig
 library's laps_awd_* state decides when the short queue leaves and in which captured shape, one replay per
 dispatch; long chunks fill the time in which the short round is still collecting.
 The baseline is the policy the paper argues against (Section 2.3): one FCFS queue, each step a
-token-budget batch that mixes the next long chunk with whatever short requests fit.
+token-budget batch that mixes the next long chunk with whatever short requests fit - with a budget of
+one chunk (a mixed, chunked batch), or with a budget that takes a long prompt whole (memory-based
+batching as Section 2.3 states it: the short requests behind a long prompt wait for all of it).
 
 Arrivals are virtual timestamps; the clock advances by the measured GPU time of every step (HIP events
 around the step, host launch overhead included when it stalls the GPU) and jumps over idle gaps.
@@ -180,7 +182,12 @@ class DualQueue:
         return res
 
     # ------------------------------------------------------------------ policies
-    def run_unified(self, arrival_us) -> DQResult:
+    def run_unified(self, arrival_us, budget: int | None = None) -> DQResult:
+        """One FCFS queue, every step a token-budget batch of whatever waits.  budget None: `unified_budget` tokens per
+        step (the head long request advances in chunks of what is left of it: a mixed, chunked batch).  A budget of at
+        least the longest prompt gives the memory-based batching of Section 2.3 as the paper states it: a long prompt
+        enters whole, together with the short requests that fit behind it."""
+        step_budget = self.p.unified_budget if budget is None else int(budget)
         arrival = np.asarray(arrival_us, np.float64)
         order = list(np.argsort(arrival, kind="stable"))
         done = np.zeros(self.n, np.int64)
@@ -194,7 +201,7 @@ class DualQueue:
             if not queue:
                 t = arrival[order[nxt]]
                 continue
-            budget, segs = self.p.unified_budget, []
+            budget, segs = step_budget, []
             for r in queue:                                   # FCFS, the head long request is chunked by what is left
                 if budget == 0:
                     break
@@ -210,7 +217,8 @@ class DualQueue:
                 if done[r] == self.new_len[r]:
                     finish[r] = t
             queue = [r for r in queue if done[r] < self.new_len[r]]
-        return DQResult("unified", t, busy, steps, finish, finish - arrival, {"mixed": steps})
+        mode = "unified" if step_budget == self.p.unified_budget else f"unified(budget={step_budget})"
+        return DQResult(mode, t, busy, steps, finish, finish - arrival, {"mixed": steps})
 
     def run_disaggregated(self, arrival_us, window_us=None) -> DQResult:
         p = self.p

@@ -414,7 +414,13 @@ def test_config5_dual_queue_step_loop(config5):
     dq.out.zero_()
     ru = dq.run_unified(zeros)
     assert_parity("config5 unified mixed batches (same requests)", st.sampled_rows(), st.sub, None, st.cache)
-    for r in (rd, ru):
+    # memory-based batching that takes long prompts whole (Section 2.3): batches of up to 16384 rows, a 2K-8K prompt
+    # and hundreds of short sequences in one launch
+    dq.out.zero_()
+    rv = dq.run_unified(zeros, budget=16384)
+    assert_parity("config5 unified, long prompts whole (same requests)", st.sampled_rows(), st.sub, None, st.cache)
+    assert rv.n_steps < ru.n_steps
+    for r in (rd, ru, rv):
         assert np.all(r.finish_us > 0) and np.all(r.latency_us > 0)
         print("[config5]", r.summary(b.new_len, is_long), flush=True)
     assert rd.step_kinds["long_chunk"] == int(sum(-(-int(l) // 2048) for l in b.new_len[is_long]))
