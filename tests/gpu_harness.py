@@ -2,6 +2,9 @@
 C-ABI binding on the device and through the fp64 oracle on the CPU, and measures the difference."""
 from __future__ import annotations
 
+import os
+import time
+
 import numpy as np
 import torch
 
@@ -10,6 +13,23 @@ from paper_2601_11589_amd import api, inputs
 
 REL_L2_TOL = 5e-3   # spec tolerance for layer / stack outputs vs the fp64 oracle
 MAX_ABS_TOL = 2e-2
+
+
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "gpu_tests_progress.log")
+
+
+def progress(msg: str):
+    """One line per finished step of a long test (an fp64 pass of the oracle takes up to a minute or two of host time),
+    printed and appended to a log file: pytest holds the printed text back until the test ends, and a harness that
+    watches for output would otherwise see nothing for the length of the longest test."""
+    line = f"{time.strftime('%H:%M:%S')} {msg}"
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS), exist_ok=True)
+        with open(_PROGRESS, "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
 
 
 def widen_layer(w_bits: dict) -> dict:
@@ -68,8 +88,11 @@ class Case:
               for l in range(self.n_layers)]
         pv = [[None if self.prefix[l][i] is None else inputs.bf16_bits_to_f64(self.prefix[l][i][1]) for i in ids]
               for l in range(self.n_layers)]
+        t0 = time.perf_counter()
         y, ks, vs = O.stack_forward(self.cfg, LazyWideLayers(self.host_layers), self.x[rows].astype(np.float64),
                                     [int(self.new_len[i]) for i in ids], pk, pv, storage_rounding)
+        progress(f"oracle pass done: {len(ids)} sequences, {len(rows)} rows, {self.n_layers} layers, "
+                 f"storage_rounding={storage_rounding}, {time.perf_counter() - t0:.1f} s")
         return y, ks, vs, rows
 
     # ---- device side
